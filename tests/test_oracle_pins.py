@@ -1,0 +1,319 @@
+"""Pins for the CPU oracle: each check ties an oracle function to something other than itself —
+an independent library routine on a special case, a brute-force evaluation of the paper's
+definition on tiny inputs, a closed form, or an invariance the mathematics fixes.
+All CPU-only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import focus_oracle as fo
+
+
+def _rand(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# --------------------------------------------------------------------------- top-k total order (Eq. 4, Top-C, Top-N_sink)
+def _brute_top(values, n, cand=None):
+    items = [(i, float(v) + 0.0) for i, v in enumerate(values) if cand is None or cand[i]]
+    items.sort(key=lambda t: (math.isnan(t[1]), -t[1] if not math.isnan(t[1]) else 0.0, t[0]))
+    return sorted(i for i, _ in items[:n])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_top_indices_matches_brute_force_sort(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 40))
+    v = rng.integers(0, 6, n).astype(np.float64)  # many ties
+    cand = rng.random(n) < 0.7
+    for k in (0, 1, n // 2, n, n + 3):
+        assert fo.top_indices(v, k).tolist() == _brute_top(v, k)
+        assert fo.top_indices(v, k, cand).tolist() == _brute_top(v, k, cand)
+
+
+def test_top_indices_exhaustive_small():
+    # every length-4 vector over {0,1,2}: the kept set is exactly the k first of the stable descending sort
+    for vals in itertools.product([0.0, 1.0, 2.0], repeat=4):
+        for k in range(5):
+            assert fo.top_indices(vals, k).tolist() == _brute_top(vals, k)
+
+
+def test_top_indices_special_values():
+    v = np.array([np.nan, -np.inf, -0.0, 0.0, np.inf, 1.0, np.nan])
+    assert fo.top_indices(v, 1).tolist() == [4]
+    assert fo.top_indices(v, 3).tolist() == [2, 4, 5]        # -0.0 ties +0.0: lower index wins
+    assert fo.top_indices(v, 5).tolist() == [1, 2, 3, 4, 5]  # -inf still beats NaN
+    assert fo.top_indices(v, 6).tolist() == [0, 1, 2, 3, 4, 5]
+    assert fo.top_indices(np.zeros(5), 2).tolist() == [0, 1]  # all equal: lowest indices
+
+
+def test_top_indices_agrees_with_torch_topk_when_no_ties():
+    v = _rand(3, 257)
+    got = fo.top_indices(v, 17)
+    ref = torch.topk(torch.from_numpy(v), 17).indices.sort().values.numpy()
+    assert got.tolist() == ref.tolist()
+
+
+def test_nested_top_sets():
+    v = _rand(4, 100)
+    prev = set()
+    for k in range(0, 101, 7):
+        cur = set(fo.top_indices(v, k).tolist())
+        assert prev <= cur and len(cur) == k
+        prev = cur
+
+
+def test_decision_margin():
+    v = np.array([5.0, 1.0, 4.0, 0.0])
+    assert fo.decision_margin(v, 2) == pytest.approx((4.0 - 1.0) / 5.0)
+    assert fo.decision_margin(v, 4) == math.inf
+    assert fo.decision_margin(np.array([1.0, 1.0, 0.0]), 1) == 0.0
+
+
+# --------------------------------------------------------------------------- stage 1 (Eq. 4, Eq. 5)
+def test_select_focus_masked_subset_and_clipping():
+    conf = np.array([0.9, 0.1, 0.8, 0.8, 0.3, 0.95], dtype=np.float32)
+    masked = np.array([1, 1, 1, 1, 1, 0], dtype=np.uint8)      # position 5 is already unmasked
+    assert fo.select_focus(conf, masked, 2).tolist() == [0, 2]  # 0.8 tie -> lower position
+    assert fo.select_focus(conf, masked, 3).tolist() == [0, 2, 3]
+    assert fo.select_focus(conf, masked, 9).tolist() == [0, 1, 2, 3, 4]  # k clipped to #masked
+    assert fo.select_focus(conf, None, 1).tolist() == [5]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_expand_window_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = 40
+    focus = np.sort(rng.choice(n, size=6, replace=False))
+    for w in (0, 1, 2, 3, 8, 9):
+        lo, hi = 3, 35
+        got = fo.expand_window(focus, w, lo, hi)
+        ref = [l for l in range(lo, hi) if any(abs(l - int(i)) <= w // 2 for i in focus)]
+        assert got.tolist() == ref
+        assert len(got) <= min(hi - lo, len(focus) * (2 * (w // 2) + 1))
+    inside = focus[(focus >= 3) & (focus < 35)]
+    assert fo.expand_window(focus, 0, 3, 35).tolist() == inside.tolist()
+    assert fo.expand_window(focus, 1, 3, 35).tolist() == inside.tolist()
+
+
+def test_expand_window_paper_default_is_nine_wide():
+    assert fo.expand_window([20], 8, 0, 64).tolist() == list(range(16, 25))
+
+
+# --------------------------------------------------------------------------- stage 2a (block means, Eq. 7)
+def test_block_means_brute_force_ragged_tail():
+    H, M, N, d, B = 2, 23, 5, 3, 8   # blocks of 8, 8, 7 prompt rows; 5 response rows must be ignored
+    K = _rand(7, H, M + N, d)
+    kb = fo.block_means(K, M, B)
+    assert kb.shape == (H, 3, d)
+    for h in range(H):
+        for b in range(3):
+            rows = range(b * B, min((b + 1) * B, M))
+            for c in range(d):
+                ref = sum(K[h, j, c] for j in rows) / len(rows)
+                assert kb[h, b, c] == pytest.approx(ref, abs=1e-14)
+
+
+def test_block_relevance_is_mean_of_pairwise_dot_products():
+    # linearity: q_bar . K_bar_b equals the mean over (i in focus, j in block) of Q_i . K_j, averaged over heads
+    H, M, N, d, B, n_gen = 3, 20, 4, 5, 6, 7
+    Q, K = _rand(8, H, n_gen, d), _rand(9, H, M + N, d)
+    focus = np.array([1, 4, 5])
+    R = fo.block_relevance(Q, focus, fo.block_means(K, M, B))
+    for b in range(4):
+        rows = list(range(b * B, min((b + 1) * B, M)))
+        acc = 0.0
+        for h in range(H):
+            for i in focus:
+                for j in rows:
+                    acc += sum(Q[h, i, c] * K[h, j, c] for c in range(d))
+        assert R[b] == pytest.approx(acc / (H * len(focus) * len(rows)), abs=1e-13)
+
+
+def test_block_relevance_scale_closed_form():
+    # all queries e_0, block b's keys all (b+1)*e_0  =>  R_b = b+1 exactly: no hidden 1/sqrt(d) or 1/|focus|
+    H, d, B, n_b = 4, 8, 5, 3
+    Q = np.zeros((H, 6, d)); Q[..., 0] = 1.0
+    K = np.zeros((H, n_b * B + 2, d))
+    for b in range(n_b):
+        K[:, b * B:(b + 1) * B, 0] = b + 1
+    R = fo.block_relevance(Q, [0, 2, 3], fo.block_means(K, n_b * B, B))
+    assert R.tolist() == [1.0, 2.0, 3.0]
+    assert fo.select_blocks(R, 2).tolist() == [1, 2]
+
+
+# --------------------------------------------------------------------------- stage 2b (Eq. 6)
+def test_sink_scores_brute_force_definition():
+    H, L, d, n_gen = 2, 6, 3, 4
+    Q, K = _rand(10, H, n_gen, d), _rand(11, H, L, d)
+    active = [0, 3]
+    S = fo.sink_scores(Q, active, K)
+    ref = [0.0] * L
+    for h in range(H):
+        for i in active:
+            logit = [sum(Q[h, i, c] * K[h, j, c] for c in range(d)) / math.sqrt(d) for j in range(L)]
+            z = sum(math.exp(x) for x in logit)
+            for j in range(L):
+                ref[j] += math.exp(logit[j]) / z / (H * len(active))
+    assert np.allclose(S, ref, atol=1e-14)
+
+
+def test_sink_scores_against_torch_softmax_and_row_sums():
+    H, L, d, n_gen = 3, 50, 16, 9
+    Q, K = _rand(12, H, n_gen, d), _rand(13, H, L, d)
+    active = np.array([0, 2, 7, 8])
+    S = fo.sink_scores(Q, active, K)
+    tq, tk = torch.from_numpy(Q)[:, active], torch.from_numpy(K)
+    P = torch.softmax(tq @ tk.transpose(1, 2) / math.sqrt(d), dim=-1)
+    assert np.allclose(S, P.mean(dim=(0, 1)).numpy(), atol=1e-14)
+    assert S.sum() == pytest.approx(1.0, abs=1e-12)           # every softmax row sums to one
+    assert (S > 0).all()
+
+
+def test_sink_scores_closed_forms():
+    H, L, d = 2, 12, 4
+    Q = _rand(14, H, 5, d)
+    K = np.tile(_rand(15, 1, 1, d), (H, L, 1))               # all keys equal -> uniform attention
+    S = fo.sink_scores(Q, [1, 2], K)
+    assert np.allclose(S, 1.0 / L, atol=1e-15)
+    assert fo.select_sinks(S + 0.0, 10, 3).tolist() == [0, 1, 2]
+    # one key aligned with every query with a huge logit -> all mass on it
+    Q2 = np.zeros((H, 3, d)); Q2[..., 0] = 30.0
+    K2 = np.zeros((H, L, d)); K2[:, 7, 0] = 30.0
+    S2 = fo.sink_scores(Q2, [0, 1, 2], K2)
+    assert S2[7] == pytest.approx(1.0, abs=1e-12)
+    assert fo.select_sinks(S2, L - 2, 1).tolist() == [7]
+
+
+def test_select_sinks_only_prompt_positions():
+    S = np.array([0.1, 0.3, 0.05, 0.2, 0.9, 0.8])  # last two are response rows
+    assert fo.select_sinks(S, 4, 2).tolist() == [1, 3]
+
+
+def test_sink_scores_key_shift_and_head_permutation_invariance():
+    H, L, d = 3, 20, 8
+    Q, K = _rand(16, H, 6, d), _rand(17, H, L, d)
+    S = fo.sink_scores(Q, [0, 5], K)
+    # adding one vector to every key shifts each row's logits by a constant: the softmax does not move
+    assert np.allclose(fo.sink_scores(Q, [0, 5], K + _rand(18, 1, 1, d)), S, atol=1e-13)
+    perm = [2, 0, 1]
+    assert np.allclose(fo.sink_scores(Q[perm], [0, 5], K[perm]), S, atol=1e-15)
+    # the other reading (pool the queries first) is a different quantity
+    assert not np.allclose(fo.sink_scores(Q, [0, 5], K, pooled_query=True), S, atol=1e-6)
+
+
+# --------------------------------------------------------------------------- stage 3 (Eq. 8, Eq. 9)
+def test_attention_index_set_membership():
+    M, B = 23, 8
+    got = fo.attention_index_set([3, 17, 22, 40, -1], [2, 0, -1], M, B)
+    ref = [j for j in range(M) if j in (3, 17, 22) or j // B in (0, 2)]
+    assert got.tolist() == ref
+    # a sink inside a kept block, or listed twice, is still one element
+    assert fo.attention_index_set([3, 3, 5], [0], M, B).tolist() == list(range(8))
+
+
+def _sdpa(Q, K, V):
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x))
+    return torch.nn.functional.scaled_dot_product_attention(t(Q), t(K), t(V)).numpy()
+
+
+def test_dense_reduction_equals_full_bidirectional_attention():
+    # keep every block, take every row as a query: the sparse path must be plain softmax(QK^T/sqrt(d))V over all L keys
+    H, M, N, d, B = 3, 37, 6, 16, 8
+    Q, K, V = _rand(20, H, 11, d), _rand(21, H, M + N, d), _rand(22, H, M + N, d)
+    n_b = -(-M // B)
+    I_p = fo.attention_index_set([], np.arange(n_b), M, B)
+    out, lse = fo.sparse_attention(Q, np.arange(11), K, V, I_p, M)
+    assert np.allclose(out, _sdpa(Q, K, V), atol=1e-13)
+    ref_lse = torch.logsumexp(torch.from_numpy(Q) @ torch.from_numpy(K).transpose(1, 2) / math.sqrt(d), dim=-1)
+    assert np.allclose(lse, ref_lse.numpy(), atol=1e-13)
+    # and through the per-layer driver with C = n_b
+    r = fo.focus_layer(Q, K, V, [0, 1], np.arange(11), [5], M, B, n_b)
+    assert np.allclose(r["out"], _sdpa(Q, K, V), atol=1e-13)
+
+
+def test_sparse_attention_equals_attention_over_gathered_rows():
+    H, M, N, d, B = 2, 40, 5, 8, 8
+    Q, K, V = _rand(23, H, 9, d), _rand(24, H, M + N, d), _rand(25, H, M + N, d)
+    I_p = fo.attention_index_set([1, 30], [2, 4], M, B)
+    rows = [j for j in range(M + N) if j >= M or j in (1, 30) or j // B in (2, 4)]
+    active = np.array([0, 4, 8])
+    out, _ = fo.sparse_attention(Q, active, K, V, I_p, M)
+    assert np.allclose(out, _sdpa(Q[:, active], K[:, rows], V[:, rows]), atol=1e-13)
+
+
+def test_sparse_attention_closed_forms():
+    H, M, N, d, B = 2, 16, 0, 4, 4
+    Q, V = _rand(26, H, 3, d), _rand(27, H, M, d)
+    K = np.tile(_rand(28, 1, 1, d), (H, M, 1))                # equal keys: output is the mean of the kept V rows
+    I_p = fo.attention_index_set([9], [1], M, B)
+    out, lse = fo.sparse_attention(Q, [0, 2], K, V, I_p, M)
+    assert np.allclose(out, V[:, [4, 5, 6, 7, 9]].mean(axis=1, keepdims=True).repeat(2, axis=1), atol=1e-14)
+    # a single kept key (no blocks, one sink, no response rows): the output is that V row exactly
+    out1, _ = fo.sparse_attention(Q, [1], _rand(29, H, M, d), V, fo.attention_index_set([11], [], M, B), M)
+    assert np.array_equal(out1[:, 0], V[:, 11])
+    # one-hot: a huge logit on one key
+    K2 = np.zeros((H, M, d)); K2[:, 6, 0] = 50.0
+    Q2 = np.zeros((H, 1, d)); Q2[..., 0] = 50.0
+    out2, _ = fo.sparse_attention(Q2, [0], K2, V, fo.attention_index_set([], [0, 1, 2], M, B), M)
+    assert np.allclose(out2[:, 0], V[:, 6], atol=1e-12)
+
+
+def test_sparse_attention_metamorphic():
+    H, M, N, d, B = 3, 32, 4, 8, 8
+    Q, K, V = _rand(30, H, 6, d), _rand(31, H, M + N, d), _rand(32, H, M + N, d)
+    sinks, blocks, active = [2, 20], [1, 3], [0, 3, 5]
+    I_p = fo.attention_index_set(sinks, blocks, M, B)
+    out, lse = fo.sparse_attention(Q, active, K, V, I_p, M)
+    assert np.array_equal(fo.sparse_attention(Q, active, K, 2 * V, I_p, M)[0], 2 * out)      # linear in V
+    assert np.allclose(fo.sparse_attention(Q, active, K + _rand(33, 1, 1, d), V, I_p, M)[0], out, atol=1e-13)
+    perm = [1, 2, 0]
+    assert np.array_equal(fo.sparse_attention(Q[perm], active, K[perm], V[perm], I_p, M)[0], out[perm])
+    assert np.array_equal(fo.attention_index_set(sinks[::-1], blocks[::-1], M, B), I_p)       # order of the sets
+    assert np.array_equal(fo.attention_index_set(sinks + [9, 9, 2], blocks, M, B), I_p)       # dedupe (9 is in block 1)
+    # softmax weights are a probability distribution: feeding V = 1 returns exactly-normalised rows
+    ones, _ = fo.sparse_attention(Q, active, K, np.ones_like(V), I_p, M)
+    assert np.allclose(ones, 1.0, atol=1e-14)
+
+
+def test_key_shift_leaves_every_selection_unchanged():
+    H, M, N, d, B = 4, 64, 8, 16, 8
+    Q, K = _rand(34, H, 8, d), _rand(35, H, M + N, d)
+    focus = [1, 2, 6]
+    delta = _rand(36, 1, 1, d)
+    R0 = fo.block_relevance(Q, focus, fo.block_means(K, M, B))
+    R1 = fo.block_relevance(Q, focus, fo.block_means(K + delta, M, B))
+    assert np.allclose(R1 - R0, (R1 - R0)[0], atol=1e-12)        # uniform shift of the scores
+    assert fo.select_blocks(R0, 3).tolist() == fo.select_blocks(R1, 3).tolist()
+    S0, S1 = fo.sink_scores(Q, focus, K), fo.sink_scores(Q, focus, K + delta)
+    assert fo.select_sinks(S0, M, 3).tolist() == fo.select_sinks(S1, M, 3).tolist()
+
+
+# --------------------------------------------------------------------------- step driver (Alg. 1): sink reuse
+def test_step_reuses_probe_layer_sinks_unchanged():
+    H, M, N, d, B, n_gen, n_layers = 2, 48, 8, 8, 8, 8, 5
+    tensors = {l: (_rand(40 + l, H, n_gen, d), _rand(50 + l, H, M + N, d), _rand(60 + l, H, M + N, d))
+               for l in range(n_layers)}
+    conf = np.random.default_rng(70).random(n_gen).astype(np.float32)
+    step = fo.focus_step(conf, None, 3, 0, 0, n_gen, lambda l: tensors[l], probe_layer=1, sparse_layers=[2, 3, 4],
+                         n_ctx=M, block=B, n_keep=2, n_sink=3)
+    Qp, Kp, _ = tensors[1]
+    assert step["sinks"].tolist() == fo.select_sinks(fo.sink_scores(Qp, step["active"], Kp), M, 3).tolist()
+    for l in (2, 3, 4):
+        lay = step["layers"][l]
+        assert lay["sinks_used"] is step["sinks"]                 # the same array object, not a recomputation
+        Q, K, V = tensors[l]
+        I_p = fo.attention_index_set(step["sinks"], lay["blocks"], M, B)
+        assert np.array_equal(lay["out"], fo.sparse_attention(Q, step["active"], K, V, I_p, M)[0])
+    # the sinks a deeper layer would find on its own differ, so reuse is not vacuous here
+    own = [fo.select_sinks(fo.sink_scores(tensors[l][0], step["active"], tensors[l][1]), M, 3).tolist() for l in (2, 3, 4)]
+    assert any(o != step["sinks"].tolist() for o in own)
+
+
+def test_widen_bf16_exact():
+    t = torch.tensor([1.0, -2.5, 0.333, 1e-30, 3e38, 0.0, -0.0], dtype=torch.bfloat16)
+    bits = t.view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(fo.widen_bf16(bits), t.to(torch.float64).numpy())
