@@ -1,0 +1,163 @@
+/*
+ * focus.h — C ABI of the Focus-dLLM sparse-attention step for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-step hot path of Focus-dLLM
+ * (arXiv 2602.02159): the past-confidence-guided query selection (Sec. 5.2), the sink-aware
+ * block pruning (Sec. 5.3) and the sparse attention over the kept keys (Eq. 9), in the order
+ * Alg. 1 runs them:
+ *
+ *     focus_select_queries   once per denoising step            -> I_focus, I_active
+ *     focus_find_sinks       once per step, at the probe layer  -> I_sink   (reused unchanged by all deeper layers)
+ *     focus_block_means      whenever the prompt K of a layer is refreshed -> K_bar (cacheable)
+ *     focus_block_scores     per sparse layer                   -> R_b, B_relevant
+ *     focus_sparse_attn      per sparse layer                   -> Attn
+ *
+ * Conventions shared by every entry point
+ *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
+ *    buffer; the library allocates and frees nothing, keeps no state between calls, and scratch memory
+ *    comes from the caller's `workspace` (size from focus_workspace_bytes()).
+ *  - Q is bf16 [H, n_gen, d]; K and V are bf16 [H, M+N, d] (rows 0..M-1 prompt, rows M..M+N-1 response);
+ *    strides are in elements, the innermost (d) stride is 1, every row start must be 16-byte aligned
+ *    (base pointers 16-byte aligned, row strides multiples of 8).
+ *  - `stream` is a hipStream_t (NULL = the null stream).  Calls only enqueue work: they never synchronise,
+ *    and index sets stay on the device from one call to the next.
+ *  - Every top-k orders by (value descending, index ascending), -0.0 equal to +0.0, NaN below every
+ *    number; index outputs are int32, ascending, and slots past the number found are set to -1.
+ *  - `counts` [dev] is int32[2] = {|I_focus|, |I_active|} as written by focus_select_queries.  Where an
+ *    entry point takes `counts`, NULL means "every slot of the index array is valid".
+ *  - Return value: a focus_status.  Arguments are validated on the host before anything is launched; on
+ *    FOCUS_EINVAL / FOCUS_EUNSUPPORTED / FOCUS_EWORKSPACE nothing has been enqueued and no output is
+ *    touched.  focus_last_error() describes the last failure of the calling thread.
+ */
+#ifndef FOCUS_H_
+#define FOCUS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum focus_status {
+  FOCUS_OK = 0,
+  FOCUS_EINVAL = -1,       /* a NULL pointer, a size or a count out of range, a misaligned stride */
+  FOCUS_EUNSUPPORTED = -2, /* a shape the kernels are not built for (head_dim other than 64 / 128, ...) */
+  FOCUS_EWORKSPACE = -3,   /* workspace NULL or smaller than focus_workspace_bytes() */
+  FOCUS_ELAUNCH = -4       /* the HIP runtime refused a launch */
+} focus_status;
+
+/* Shape of one layer's tensors.  All strides in elements. */
+typedef struct focus_shape {
+  int32_t n_heads;  /* H */
+  int32_t head_dim; /* d: 64 or 128 */
+  int32_t n_ctx;    /* M: prompt rows of K/V; the only rows block pruning and sink selection consider */
+  int32_t n_resp;   /* N: response rows M..M+N-1 of K/V, always attended (Sec. 5.3) */
+  int32_t block;    /* B: prompt block size; block b = rows [b*B, min((b+1)*B, M)) */
+  int32_t n_gen;    /* rows of Q (positions of the current generation block) */
+  int64_t q_stride_h, q_stride_n;
+  int64_t k_stride_h, k_stride_n;
+  int64_t v_stride_h, v_stride_n;
+  int64_t o_stride_h, o_stride_n; /* output of focus_sparse_attn, bf16 [H, max_active, d] */
+} focus_shape;
+
+/* Which entry point a workspace size is asked for. */
+typedef enum focus_fn {
+  FOCUS_FN_BLOCK_SCORES = 1,
+  FOCUS_FN_FIND_SINKS = 2,
+  FOCUS_FN_SPARSE_ATTN = 3
+} focus_fn;
+
+/*
+ * Past-confidence-guided indicator (Sec. 5.2, Eq. 4) and window expansion (Eq. 5).
+ *   conf   [dev] fp32[n_gen]  previous-step confidence of each position of the current block
+ *   masked [dev] u8[n_gen]    non-zero = still masked (a candidate); NULL = all masked
+ *   k                         size of I_focus asked for (= round(rho * n_unmask)); 1 <= k <= n_gen.
+ *                             |I_focus| = min(k, #masked).
+ *   window                    w of Eq. 5; each focus position i contributes [i - w/2, i + w/2] (integer
+ *                             division), clipped to [lo, hi), 0 <= lo < hi <= n_gen.  w <= 1: I_active = I_focus
+ *                             clipped to [lo, hi).
+ *   focus_idx  [dev] int32[k]           out: I_focus
+ *   active_idx [dev] int32[max_active]  out: I_active; max_active >= min(hi-lo, k*(2*(w/2)+1)) is required
+ *   counts     [dev] int32[2]           out: {|I_focus|, |I_active|}
+ * n_gen <= 16384.
+ */
+int focus_select_queries(const float* conf, const uint8_t* masked, int32_t n_gen, int32_t k, int32_t window,
+                         int32_t lo, int32_t hi, int32_t* focus_idx, int32_t* active_idx, int32_t max_active,
+                         int32_t* counts, void* stream);
+
+/*
+ * Representative key of every prompt block (Sec. 5.3, "Block-wise token pruning"):
+ *   kbar[h, b, :] = mean over the rows of block b of K[h, :, :]      fp32 [H, n_b, d], n_b = ceil(M / B)
+ * The last block is averaged over its true length.  Prompt K is frozen between block-entry refreshes
+ * (Eq. 3), so the result may be cached by the caller and passed to focus_block_scores.
+ */
+int focus_block_means(const void* K, const focus_shape* shape, float* kbar, void* stream);
+
+/*
+ * Block relevance (Eq. 7) and B_relevant = Top-C (Sec. 5.3).
+ *   R_b = (1/H) sum_h qbar^h . kbar^h_b,  qbar^h = mean over I_focus of Q[h, i, :]   (fp32 throughout)
+ *   Q          [dev] bf16 [H, n_gen, d]
+ *   focus_idx  [dev] int32[n_focus_max] rows of Q; counts[0] (or n_focus_max if counts is NULL) are valid
+ *   kbar       [dev] fp32 [H, n_b, d] from focus_block_means, or NULL: then K [dev] is scanned first and the
+ *              means are built in the workspace (K may be NULL when kbar is given)
+ *   n_keep     C, 0 <= C <= n_b (pass floor(alpha * n_b) — see focus_helper_n_keep)
+ *   scores     [dev] fp32[n_b] out, may be NULL
+ *   kept_blocks[dev] int32[n_keep] out, ascending block ids
+ */
+int focus_block_scores(const void* Q, const int32_t* focus_idx, const int32_t* counts, int32_t n_focus_max,
+                       const void* K, const float* kbar, const focus_shape* shape, int32_t n_keep, float* scores,
+                       int32_t* kept_blocks, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Dynamic attention-sink identification at the probe layer (Sec. 5.3, Eq. 6).
+ *   P[h, i, :] = softmax over all M+N keys of Q[h, i] . K[h, j] / sqrt(d), i in I_active
+ *   S_j        = mean over heads and active queries of P[h, i, j]           (column attention mass)
+ *   I_sink     = the n_sink prompt positions (j < M) with the largest S_j
+ *   active_idx [dev] int32[max_active]; counts[1] (or max_active if counts is NULL) entries are valid
+ *   col_mass   [dev] fp32[M+N] out, may be NULL
+ *   sink_idx   [dev] int32[n_sink] out, ascending; 0 <= n_sink <= M.  Pass this buffer unchanged to
+ *              focus_sparse_attn of every deeper layer (cross-layer reuse, Sec. 5.3).
+ * With no active query S is defined as 0 and the lowest positions are returned.
+ */
+int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active,
+                     const void* K, const focus_shape* shape, int32_t n_sink, float* col_mass, int32_t* sink_idx,
+                     void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Sink-aware sparse attention (Sec. 5.3, Eq. 8 and Eq. 9).
+ *   I_p  = I_sink  united with  all rows of the kept blocks          (a set: a sink inside a kept block, a
+ *          repeated entry, and entries < 0 or outside the prompt are attended once / ignored)
+ *   out[h, a, :] = softmax_j(Q[h, i_a] . K[h, j] / sqrt(d)) . V[h, j, :],  j over I_p and the N response rows,
+ *          for the a-th active query i_a; bidirectional, no mask.
+ *   kept_blocks [dev] int32[n_keep], sink_idx [dev] int32[n_sink] (either may be NULL when its count is 0)
+ *   out  [dev] bf16 [H, max_active, d] with strides o_stride_*; rows a >= |I_active| are not written
+ *   lse  [dev] fp32 [H, max_active] natural-log sum of exp of the scaled logits, may be NULL
+ * n_keep = n_b with every row active gives dense bidirectional attention (the comparison baseline).
+ * If the key set is empty (n_keep = 0, no valid sink, N = 0) the output rows are zero and lse is -inf.
+ */
+int focus_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active,
+                      const void* K, const void* V, const focus_shape* shape, const int32_t* kept_blocks,
+                      int32_t n_keep, const int32_t* sink_idx, int32_t n_sink, void* out, float* lse,
+                      void* workspace, size_t ws_bytes, void* stream);
+
+/* Bytes of workspace `fn` needs for this shape; 0 on invalid arguments.  [host] only. */
+size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep,
+                             int32_t n_sink);
+
+/* Host helpers for the integer hyper-parameters, evaluated in double so that caller and checker agree:
+ * k = floor(rho * n_unmask + 0.5) (Eq. 4), C = floor(alpha * n_blocks) (Sec. 5.3), N_sink = floor(frac * M). */
+int32_t focus_helper_k(double rho, int32_t n_unmask);
+int32_t focus_helper_n_keep(double alpha, int32_t n_blocks);
+int32_t focus_helper_n_sink(double frac, int32_t n_ctx);
+
+/* Description of the calling thread's last failure ("" if none); static storage, never freed. */
+const char* focus_last_error(void);
+
+/* Library version string, static storage. */
+const char* focus_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOCUS_H_ */

@@ -1,0 +1,165 @@
+"""ctypes binding of libfocus_hip.so: argument marshalling only.
+
+Every function has the name of the C entry point it wraps (include/focus.h) minus the `focus_` prefix of
+the status code: it takes torch CUDA tensors, passes their device pointers, sizes and strides through, and
+raises FocusError on a non-zero status.  No step of the method runs in Python, and there is no fallback:
+if the HIP library is not built, importing this module's `lib()` fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfocus_hip.so")
+
+FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0, -1, -2, -3, -4
+FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN = 1, 2, 3
+
+EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
+           "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
+           "focus_version")
+
+
+class FocusError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"focus status {status}: {message}")
+        self.status = status
+
+
+class Shape(C.Structure):
+    """Mirror of `focus_shape`."""
+    _fields_ = [("n_heads", C.c_int32), ("head_dim", C.c_int32), ("n_ctx", C.c_int32), ("n_resp", C.c_int32),
+                ("block", C.c_int32), ("n_gen", C.c_int32),
+                ("q_stride_h", C.c_int64), ("q_stride_n", C.c_int64), ("k_stride_h", C.c_int64), ("k_stride_n", C.c_int64),
+                ("v_stride_h", C.c_int64), ("v_stride_n", C.c_int64), ("o_stride_h", C.c_int64), ("o_stride_n", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2602_02159_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -m paper_2602_02159_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        p, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        sp = C.POINTER(Shape)
+        L.focus_select_queries.argtypes = [p, p, i32, i32, i32, i32, i32, p, p, i32, p, p]
+        L.focus_block_means.argtypes = [p, sp, p, p]
+        L.focus_block_scores.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, sz, p]
+        L.focus_find_sinks.argtypes = [p, p, p, i32, p, sp, i32, p, p, p, sz, p]
+        L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
+        for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
+                     "focus_sparse_attn"):
+            getattr(L, name).restype = C.c_int
+        L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
+        L.focus_workspace_bytes.restype = sz
+        L.focus_helper_k.argtypes = [C.c_double, i32]
+        L.focus_helper_k.restype = i32
+        L.focus_helper_n_keep.argtypes = [C.c_double, i32]
+        L.focus_helper_n_keep.restype = i32
+        L.focus_helper_n_sink.argtypes = [C.c_double, i32]
+        L.focus_helper_n_sink.restype = i32
+        L.focus_last_error.restype = C.c_char_p
+        L.focus_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().focus_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != FOCUS_OK:
+        raise FocusError(status, last_error())
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _need(t: torch.Tensor, dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype:
+        raise TypeError(f"{name}: expected a CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+
+
+def make_shape(q: torch.Tensor, k: torch.Tensor | None, v: torch.Tensor | None, n_ctx: int, block: int,
+               out: torch.Tensor | None = None) -> Shape:
+    """focus_shape from [H, rows, d] tensors (any strides with a unit innermost stride)."""
+    H, n_gen, d = q.shape
+    s = Shape()
+    s.n_heads, s.head_dim, s.n_gen, s.block, s.n_ctx = H, d, n_gen, block, n_ctx
+    ref = k if k is not None else v
+    s.n_resp = (ref.shape[1] - n_ctx) if ref is not None else 0
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", out)):
+        if t is None:
+            continue
+        if t.stride(2) != 1:
+            raise ValueError(f"{name}: innermost stride must be 1")
+        setattr(s, f"{name}_stride_h", t.stride(0))
+        setattr(s, f"{name}_stride_n", t.stride(1))
+    return s
+
+
+def workspace_bytes(fn: int, shape: Shape, max_active: int = 1, n_keep: int = 0, n_sink: int = 0) -> int:
+    return int(lib().focus_workspace_bytes(fn, C.byref(shape), max_active, n_keep, n_sink))
+
+
+def helper_k(rho: float, n_unmask: int) -> int:
+    return int(lib().focus_helper_k(rho, n_unmask))
+
+
+def helper_n_keep(alpha: float, n_blocks: int) -> int:
+    return int(lib().focus_helper_n_keep(alpha, n_blocks))
+
+
+def helper_n_sink(frac: float, n_ctx: int) -> int:
+    return int(lib().focus_helper_n_sink(frac, n_ctx))
+
+
+def select_queries(conf, masked, k: int, window: int, lo: int, hi: int, focus_idx, active_idx, counts) -> None:
+    _need(conf, torch.float32, "conf")
+    _check(lib().focus_select_queries(_ptr(conf), _ptr(masked), conf.numel(), k, window, lo, hi, _ptr(focus_idx),
+                                      _ptr(active_idx), active_idx.numel(), _ptr(counts), _stream()))
+
+
+def block_means(k, shape: Shape, kbar) -> None:
+    _need(k, torch.bfloat16, "K")
+    _check(lib().focus_block_means(_ptr(k), C.byref(shape), _ptr(kbar), _stream()))
+
+
+def block_scores(q, focus_idx, counts, k, kbar, shape: Shape, n_keep: int, scores, kept_blocks, workspace) -> None:
+    _need(q, torch.bfloat16, "Q")
+    _check(lib().focus_block_scores(_ptr(q), _ptr(focus_idx), _ptr(counts), focus_idx.numel(), _ptr(k), _ptr(kbar),
+                                    C.byref(shape), n_keep, _ptr(scores), _ptr(kept_blocks), _ptr(workspace),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def find_sinks(q, active_idx, counts, k, shape: Shape, n_sink: int, col_mass, sink_idx, workspace) -> None:
+    _need(q, torch.bfloat16, "Q")
+    _need(k, torch.bfloat16, "K")
+    _check(lib().focus_find_sinks(_ptr(q), _ptr(active_idx), _ptr(counts), active_idx.numel(), _ptr(k), C.byref(shape),
+                                  n_sink, _ptr(col_mass), _ptr(sink_idx), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sparse_attn(q, active_idx, counts, k, v, shape: Shape, kept_blocks, n_keep: int, sink_idx, n_sink: int, out, lse,
+                workspace) -> None:
+    _need(q, torch.bfloat16, "Q")
+    _need(k, torch.bfloat16, "K")
+    _need(v, torch.bfloat16, "V")
+    _need(out, torch.bfloat16, "out")
+    _check(lib().focus_sparse_attn(_ptr(q), _ptr(active_idx), _ptr(counts), active_idx.numel(), _ptr(k), _ptr(v),
+                                   C.byref(shape), _ptr(kept_blocks), n_keep, _ptr(sink_idx), n_sink, _ptr(out), _ptr(lse),
+                                   _ptr(workspace),
+                                   0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))

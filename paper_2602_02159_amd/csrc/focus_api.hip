@@ -1,0 +1,276 @@
+// extern "C" boundary: argument validation on the host, workspace carving, launch sequencing.
+// Nothing here touches the GPU before every argument has been checked.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "focus_kernels.h"
+
+namespace focus {
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static int launch_fail(const char* what, hipError_t e) {
+  return fail(FOCUS_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
+}
+
+static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  const int x = atoi(v);
+  return x > 0 ? x : dflt;
+}
+
+static void plan_queries(SplitPlan& p, int max_active) {
+  p.q_tiles = ceil_div(max_active, kQTile);
+  p.q_tiles_per_group = p.q_tiles <= 1 ? 1 : (p.q_tiles == 2 ? 2 : kMaxQTilesPerGroup);
+  p.q_groups = ceil_div(p.q_tiles, p.q_tiles_per_group);
+  p.q_pad = p.q_groups * p.q_tiles_per_group * kQTile;
+}
+
+static void plan_splits(SplitPlan& p, int n_heads, int target_groups) {
+  const int per_head = target_groups / (n_heads * p.q_groups);
+  int per = ceil_div(p.n_sub, per_head > 0 ? per_head : 1);
+  per = ceil_div(per > 0 ? per : 1, kWavesPerGroup) * kWavesPerGroup;  // every wavefront gets a sub-tile
+  p.per_split = per;
+  p.n_split = p.n_sub > 0 ? ceil_div(p.n_sub, per) : 1;
+}
+
+SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n_sink) {
+  SplitPlan p;
+  plan_queries(p, max_active);
+  p.n_sub = n_keep * ceil_div(s.block, kSubTile) + ceil_div(s.n_resp, kSubTile) + ceil_div(n_sink, kSubTile);
+  plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS", 1024));
+  return p;
+}
+
+SplitPlan plan_logits(const focus_shape& s, int max_active) {
+  SplitPlan p;
+  plan_queries(p, max_active);
+  p.n_sub = ceil_div(s.n_ctx + s.n_resp, kSubTile);
+  plan_splits(p, s.n_heads, env_int("FOCUS_LOGIT_GROUPS", 2048));
+  return p;
+}
+
+// ---- validation helpers -------------------------------------------------------------------------------
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_shape(const focus_shape* s, bool need_q, bool need_k, bool need_v, bool need_o) {
+  if (!s) return fail(FOCUS_EINVAL, "shape is NULL");
+  if (s->n_heads < 1 || s->n_ctx < 1 || s->n_resp < 0 || s->block < 1 || s->n_gen < 1)
+    return fail(FOCUS_EINVAL, "shape: n_heads=%d n_ctx=%d n_resp=%d block=%d n_gen=%d out of range", s->n_heads,
+                s->n_ctx, s->n_resp, s->block, s->n_gen);
+  if (s->head_dim != 64 && s->head_dim != 128)
+    return fail(FOCUS_EUNSUPPORTED, "head_dim=%d: only 64 and 128 are built", s->head_dim);
+  if ((int64_t)s->n_ctx + s->n_resp > (1 << 30)) return fail(FOCUS_EUNSUPPORTED, "more than 2^30 key rows");
+  const int64_t d = s->head_dim, L = (int64_t)s->n_ctx + s->n_resp;
+  auto bad = [&](int64_t sh, int64_t sn, int64_t) { return sn < d || (sn & 7) || sh < 0 || (sh & 7); };
+  if (need_q && bad(s->q_stride_h, s->q_stride_n, s->n_gen)) return fail(FOCUS_EINVAL, "Q strides invalid or not multiples of 8");
+  if (need_k && bad(s->k_stride_h, s->k_stride_n, L)) return fail(FOCUS_EINVAL, "K strides invalid or not multiples of 8");
+  if (need_v && bad(s->v_stride_h, s->v_stride_n, L)) return fail(FOCUS_EINVAL, "V strides invalid or not multiples of 8");
+  if (need_o && (s->o_stride_n < d || (s->o_stride_n & 7) || (s->o_stride_h & 7)))
+    return fail(FOCUS_EINVAL, "output strides invalid or not multiples of 8");
+  return FOCUS_OK;
+}
+
+static size_t ws_block_scores(const focus_shape& s) {
+  const size_t n_b = ceil_div(s.n_ctx, s.block);
+  return align_up((size_t)s.n_heads * n_b * s.head_dim * sizeof(float)) + align_up(n_b * sizeof(float));
+}
+
+struct SinkWs {
+  size_t logits, part_ml, lse2, col_mass, total;
+};
+static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
+  SinkWs w;
+  const size_t L = (size_t)s.n_ctx + s.n_resp;
+  w.logits = 0;
+  size_t off = align_up((size_t)s.n_heads * L * p.q_pad * sizeof(float));
+  w.part_ml = off;
+  off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
+  w.lse2 = off;
+  off += align_up((size_t)s.n_heads * p.q_pad * sizeof(float));
+  w.col_mass = off;
+  off += align_up(L * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+struct AttnWs {
+  size_t part_o, part_ml, total;
+};
+static AttnWs ws_attn(const focus_shape& s, const SplitPlan& p) {
+  AttnWs w;
+  w.part_o = 0;
+  size_t off = align_up((size_t)s.n_heads * p.q_pad * p.n_split * s.head_dim * sizeof(float));
+  w.part_ml = off;
+  off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+}  // namespace focus
+
+using namespace focus;
+
+extern "C" {
+
+const char* focus_last_error(void) { return g_err; }
+const char* focus_version(void) { return "focus-gfx950 0.1"; }
+
+int32_t focus_helper_k(double rho, int32_t n_unmask) { return (int32_t)std::floor(rho * (double)n_unmask + 0.5); }
+int32_t focus_helper_n_keep(double alpha, int32_t n_blocks) { return (int32_t)std::floor(alpha * (double)n_blocks); }
+int32_t focus_helper_n_sink(double frac, int32_t n_ctx) { return (int32_t)std::floor(frac * (double)n_ctx); }
+
+size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep, int32_t n_sink) {
+  if (check_shape(shape, false, false, false, false) != FOCUS_OK) return 0;
+  const int n_b = ceil_div(shape->n_ctx, shape->block);
+  switch (fn) {
+    case FOCUS_FN_BLOCK_SCORES:
+      return ws_block_scores(*shape);
+    case FOCUS_FN_FIND_SINKS:
+      if (max_active < 1 || max_active > shape->n_gen) return 0;
+      return ws_find_sinks(*shape, plan_logits(*shape, max_active)).total;
+    case FOCUS_FN_SPARSE_ATTN:
+      if (max_active < 1 || max_active > shape->n_gen || n_keep < 0 || n_keep > n_b || n_sink < 0 ||
+          n_sink > shape->n_ctx)
+        return 0;
+      return ws_attn(*shape, plan_attention(*shape, max_active, n_keep, n_sink)).total;
+    default:
+      fail(FOCUS_EINVAL, "focus_workspace_bytes: unknown function id %d", fn);
+      return 0;
+  }
+}
+
+int focus_select_queries(const float* conf, const uint8_t* masked, int32_t n_gen, int32_t k, int32_t window, int32_t lo,
+                         int32_t hi, int32_t* focus_idx, int32_t* active_idx, int32_t max_active, int32_t* counts,
+                         void* stream) {
+  if (!conf || !focus_idx || !active_idx || !counts) return fail(FOCUS_EINVAL, "focus_select_queries: NULL pointer");
+  if (n_gen < 1 || n_gen > 16384) return fail(FOCUS_EINVAL, "focus_select_queries: n_gen=%d not in [1, 16384]", n_gen);
+  if (k < 1 || k > n_gen) return fail(FOCUS_EINVAL, "focus_select_queries: k=%d not in [1, n_gen=%d]", k, n_gen);
+  if (window < 0) return fail(FOCUS_EINVAL, "focus_select_queries: window=%d negative", window);
+  if (lo < 0 || hi > n_gen || lo >= hi) return fail(FOCUS_EINVAL, "focus_select_queries: [lo=%d, hi=%d) not inside [0, %d)", lo, hi, n_gen);
+  const int64_t span = 2 * (int64_t)(window / 2) + 1;
+  const int64_t need = std::min<int64_t>(hi - lo, (int64_t)k * span);
+  if (max_active < need) return fail(FOCUS_EINVAL, "focus_select_queries: max_active=%d < %lld", max_active, (long long)need);
+  hipError_t e = launch_select_queries(conf, masked, n_gen, k, window, lo, hi, focus_idx, active_idx, max_active, counts,
+                                       static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_select_queries", e);
+  return FOCUS_OK;
+}
+
+int focus_block_means(const void* K, const focus_shape* shape, float* kbar, void* stream) {
+  if (int rc = check_shape(shape, false, true, false, false)) return rc;
+  if (!K || !kbar) return fail(FOCUS_EINVAL, "focus_block_means: NULL pointer");
+  if (!aligned16(K) || !aligned16(kbar)) return fail(FOCUS_EINVAL, "focus_block_means: pointers must be 16-byte aligned");
+  hipError_t e = launch_block_means(K, *shape, kbar, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_block_means", e);
+  return FOCUS_OK;
+}
+
+int focus_block_scores(const void* Q, const int32_t* focus_idx, const int32_t* counts, int32_t n_focus_max, const void* K,
+                       const float* kbar, const focus_shape* shape, int32_t n_keep, float* scores, int32_t* kept_blocks,
+                       void* workspace, size_t ws_bytes, void* stream) {
+  if (int rc = check_shape(shape, true, kbar == nullptr, false, false)) return rc;
+  if (!Q || !focus_idx) return fail(FOCUS_EINVAL, "focus_block_scores: NULL pointer");
+  if (!kbar && !K) return fail(FOCUS_EINVAL, "focus_block_scores: both kbar and K are NULL");
+  const int n_b = ceil_div(shape->n_ctx, shape->block);
+  if (n_focus_max < 1 || n_focus_max > shape->n_gen) return fail(FOCUS_EINVAL, "focus_block_scores: n_focus_max=%d not in [1, n_gen]", n_focus_max);
+  if (n_keep < 0 || n_keep > n_b) return fail(FOCUS_EINVAL, "focus_block_scores: n_keep=%d not in [0, n_b=%d]", n_keep, n_b);
+  if (n_keep > 0 && !kept_blocks) return fail(FOCUS_EINVAL, "focus_block_scores: kept_blocks is NULL");
+  if (!aligned16(Q) || (kbar && !aligned16(kbar)) || (!kbar && !aligned16(K)))
+    return fail(FOCUS_EINVAL, "focus_block_scores: pointers must be 16-byte aligned");
+  if (!workspace || ws_bytes < ws_block_scores(*shape) || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "focus_block_scores: workspace needs %zu bytes, 16-byte aligned", ws_block_scores(*shape));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* ws_kbar = reinterpret_cast<float*>(ws);
+  float* ws_scores = reinterpret_cast<float*>(ws + align_up((size_t)shape->n_heads * n_b * shape->head_dim * sizeof(float)));
+  hipError_t e;
+  if (!kbar) {
+    e = launch_block_means(K, *shape, ws_kbar, st);
+    if (e != hipSuccess) return launch_fail("focus_block_scores(block means)", e);
+    kbar = ws_kbar;
+  }
+  float* R = scores ? scores : ws_scores;
+  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, R, st);
+  if (e != hipSuccess) return launch_fail("focus_block_scores(relevance)", e);
+  if (n_keep > 0) {
+    e = launch_topk(R, n_b, n_keep, kept_blocks, st);
+    if (e != hipSuccess) return launch_fail("focus_block_scores(top-C)", e);
+  }
+  return FOCUS_OK;
+}
+
+int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active, const void* K,
+                     const focus_shape* shape, int32_t n_sink, float* col_mass, int32_t* sink_idx, void* workspace,
+                     size_t ws_bytes, void* stream) {
+  if (int rc = check_shape(shape, true, true, false, false)) return rc;
+  if (!Q || !active_idx || !K) return fail(FOCUS_EINVAL, "focus_find_sinks: NULL pointer");
+  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "focus_find_sinks: max_active=%d not in [1, n_gen]", max_active);
+  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "focus_find_sinks: n_sink=%d not in [0, n_ctx]", n_sink);
+  if (n_sink > 0 && !sink_idx) return fail(FOCUS_EINVAL, "focus_find_sinks: sink_idx is NULL");
+  if (!aligned16(Q) || !aligned16(K)) return fail(FOCUS_EINVAL, "focus_find_sinks: pointers must be 16-byte aligned");
+  const SplitPlan p = plan_logits(*shape, max_active);
+  const SinkWs w = ws_find_sinks(*shape, p);
+  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "focus_find_sinks: workspace needs %zu bytes, 16-byte aligned", w.total);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* logits = reinterpret_cast<float*>(ws + w.logits);
+  float* part_ml = reinterpret_cast<float*>(ws + w.part_ml);
+  float* lse2 = reinterpret_cast<float*>(ws + w.lse2);
+  float* S = col_mass ? col_mass : reinterpret_cast<float*>(ws + w.col_mass);
+  const int L = shape->n_ctx + shape->n_resp;
+  hipError_t e = launch_qk_logits(Q, active_idx, counts, max_active, K, *shape, p, logits, part_ml, st);
+  if (e != hipSuccess) return launch_fail("focus_find_sinks(logits)", e);
+  e = launch_lse_combine(part_ml, shape->n_heads, p.q_pad, p.n_split, lse2, st);
+  if (e != hipSuccess) return launch_fail("focus_find_sinks(lse)", e);
+  e = launch_column_mass(logits, lse2, counts, max_active, shape->n_heads, L, p.q_pad, S, st);
+  if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
+  if (n_sink > 0) {
+    e = launch_topk(S, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N)", e);
+  }
+  return FOCUS_OK;
+}
+
+int focus_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active, const void* K,
+                      const void* V, const focus_shape* shape, const int32_t* kept_blocks, int32_t n_keep,
+                      const int32_t* sink_idx, int32_t n_sink, void* out, float* lse, void* workspace, size_t ws_bytes,
+                      void* stream) {
+  if (int rc = check_shape(shape, true, true, true, true)) return rc;
+  if (!Q || !active_idx || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_sparse_attn: NULL pointer");
+  const int n_b = ceil_div(shape->n_ctx, shape->block);
+  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "focus_sparse_attn: max_active=%d not in [1, n_gen]", max_active);
+  if (n_keep < 0 || n_keep > n_b) return fail(FOCUS_EINVAL, "focus_sparse_attn: n_keep=%d not in [0, n_b=%d]", n_keep, n_b);
+  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "focus_sparse_attn: n_sink=%d not in [0, n_ctx]", n_sink);
+  if ((n_keep > 0 && !kept_blocks) || (n_sink > 0 && !sink_idx)) return fail(FOCUS_EINVAL, "focus_sparse_attn: index array is NULL");
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out))
+    return fail(FOCUS_EINVAL, "focus_sparse_attn: pointers must be 16-byte aligned");
+  const SplitPlan p = plan_attention(*shape, max_active, n_keep, n_sink);
+  const AttnWs w = ws_attn(*shape, p);
+  if (p.n_split > 1 && (!workspace || ws_bytes < w.total || !aligned16(workspace)))
+    return fail(FOCUS_EWORKSPACE, "focus_sparse_attn: workspace needs %zu bytes, 16-byte aligned", w.total);
+  char* ws = static_cast<char*>(workspace);
+  hipError_t e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, kept_blocks, n_keep, sink_idx, n_sink, p,
+                                    out, lse, ws ? reinterpret_cast<float*>(ws + w.part_o) : nullptr,
+                                    ws ? reinterpret_cast<float*>(ws + w.part_ml) : nullptr,
+                                    static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_sparse_attn", e);
+  return FOCUS_OK;
+}
+
+}  // extern "C"

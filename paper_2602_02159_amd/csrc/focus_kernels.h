@@ -1,0 +1,53 @@
+// Host-side launch functions of the kernels (one per kernel family) and the launch-shape helpers the
+// API layer and the workspace-size query share.  Internal to the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/focus.h"
+
+namespace focus {
+
+constexpr int kSubTile = 32;        // keys one wavefront stages and multiplies at a time
+constexpr int kWavesPerGroup = 4;   // wavefronts per workgroup of the MFMA kernels
+constexpr int kQTile = 16;          // queries per MFMA tile
+constexpr int kMaxQTilesPerGroup = 4;
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// How the key axis of an MFMA kernel is cut: n_sub sub-tiles per head, `per_split` consecutive sub-tiles
+// per workgroup, n_split workgroups per (head, query group).
+struct SplitPlan {
+  int n_sub, per_split, n_split;
+  int q_tiles, q_tiles_per_group, q_groups, q_pad;  // q_pad = 16 * q_tiles
+};
+
+SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n_sink);
+SplitPlan plan_logits(const focus_shape& s, int max_active);
+
+// ---- small kernels (focus_small.hip)
+hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n_gen, int k, int window, int lo,
+                                 int hi, int32_t* focus_idx, int32_t* active_idx, int max_active, int32_t* counts,
+                                 hipStream_t st);
+hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, hipStream_t st);
+hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const int32_t* counts, int n_focus_max,
+                                  const float* kbar, const focus_shape& s, float* scores, hipStream_t st);
+// top-k over values[0..n): out[k] ascending indices
+hipError_t launch_topk(const float* values, int n, int k, int32_t* out, hipStream_t st);
+hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_split, float* lse2, hipStream_t st);
+hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active,
+                              int H, int L, int q_pad, float* col_mass, hipStream_t st);
+
+// ---- MFMA kernels (focus_mfma.hip)
+hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
+                            const void* K, const focus_shape& s, const SplitPlan& p, float* logits, float* part_ml,
+                            hipStream_t st);
+hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
+                              const void* K, const void* V, const focus_shape& s, const int32_t* kept_blocks,
+                              int n_keep, const int32_t* sink_idx, int n_sink, const SplitPlan& p, void* out,
+                              float* lse, float* part_o, float* part_ml, hipStream_t st);
+
+}  // namespace focus

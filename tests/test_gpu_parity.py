@@ -1,0 +1,301 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+Index outputs must be bit-exact; bf16 attention outputs within max-abs 2e-2 / mean-abs 2e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import focus_inputs as fi
+from oracle import focus_oracle as fo
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G(gpu_device):
+    from tests import gpu_util
+    return gpu_util
+
+
+def _rand_bf16(seed, *shape, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(*shape, generator=g) * scale).to(torch.bfloat16)
+
+
+# ------------------------------------------------------------------------------------------------ stage 1
+@pytest.mark.parametrize("n_gen,k,window", [(32, 8, 0), (64, 16, 0), (64, 16, 8), (64, 16, 9), (200, 7, 3), (256, 256, 0),
+                                            (1000, 100, 2), (1024, 5, 1), (1500, 300, 4), (5000, 1, 0), (16384, 4000, 8)])
+def test_select_queries(G, n_gen, k, window):
+    rng = np.random.default_rng(n_gen * 31 + k)
+    conf = rng.random(n_gen).astype(np.float32)
+    conf[rng.integers(0, n_gen, n_gen // 4)] = 0.5          # plenty of exact ties
+    masked = (rng.random(n_gen) < 0.8).astype(np.uint8)
+    for m in (None, masked):
+        for lo, hi in ((0, n_gen), (n_gen // 5, n_gen - n_gen // 7)):
+            focus, active, counts = G.gpu_select(conf, m, k, window, lo, hi)
+            ref_f = fo.select_focus(conf, m, k)
+            ref_a = fo.expand_window(ref_f, window, lo, hi)
+            c = counts.cpu().tolist()
+            assert c == [len(ref_f), len(ref_a)]
+            assert focus.cpu().tolist() == ref_f.tolist() + [-1] * (k - len(ref_f))
+            assert active.cpu().tolist()[:len(ref_a)] == ref_a.tolist()
+            assert set(active.cpu().tolist()[len(ref_a):]) <= {-1}
+
+
+def test_select_queries_special_values(G):
+    conf = np.array([np.nan, -np.inf, -0.0, 0.0, np.inf, 1.0, np.nan, 0.0], dtype=np.float32)
+    for k in range(1, 9):
+        focus, _, counts = G.gpu_select(conf, None, k, 0, 0, 8)
+        assert focus.cpu().tolist()[:k] == fo.select_focus(conf, None, k).tolist()
+    focus, active, counts = G.gpu_select(np.zeros(64, np.float32), np.zeros(64, np.uint8), 16, 8, 0, 64)
+    assert counts.cpu().tolist() == [0, 0] and set(focus.cpu().tolist()) == {-1} and set(active.cpu().tolist()) == {-1}
+
+
+@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx32k"])
+def test_select_queries_on_workloads(G, name):
+    w = fi.WORKLOADS[name]
+    conf = fi.confidence(w).numpy()
+    focus, active, counts = G.gpu_select(conf, fi.masked_all(w).numpy(), w.k_focus, w.window, 0, w.n_gen)
+    ref = fo.select_focus(conf, None, w.k_focus)
+    assert focus.cpu().tolist() == ref.tolist() and active.cpu().tolist() == ref.tolist()
+    assert counts.cpu().tolist() == [w.k_focus, w.k_focus]
+
+
+# ------------------------------------------------------------------------------------------------ stage 2a
+@pytest.mark.parametrize("H,M,N,d,B", [(2, 100, 7, 64, 16), (3, 1000, 40, 128, 128), (4, 1024, 32, 64, 64),
+                                       (2, 777, 0, 128, 50), (1, 5, 3, 128, 128)])
+def test_block_means(G, H, M, N, d, B):
+    k = _rand_bf16(1, H, M + N, d).to(G.DEV)
+    kbar = G.gpu_block_means(k, M, B)
+    ref = fo.block_means(G.to_np(k), M, B)
+    assert np.allclose(kbar.cpu().numpy(), ref, rtol=0, atol=2e-6 * math.sqrt(B))
+
+
+def test_block_means_strided_layout(G):
+    # K stored as [L, H, d] and viewed as [H, L, d]: head stride d, row stride H*d
+    H, M, N, d, B = 4, 300, 20, 128, 64
+    k = _rand_bf16(2, M + N, H, d).to(G.DEV).permute(1, 0, 2)
+    assert not k.is_contiguous()
+    ref = fo.block_means(G.to_np(k), M, B)
+    assert np.allclose(G.gpu_block_means(k, M, B).cpu().numpy(), ref, atol=2e-5)
+
+
+def test_block_scores_and_top_c(G):
+    H, M, N, d, B, n_gen = 8, 2000, 24, 128, 64, 48
+    q, k = _rand_bf16(3, H, n_gen, d).to(G.DEV), _rand_bf16(4, H, M + N, d).to(G.DEV)
+    focus = [1, 5, 9, 20, 47]
+    n_b = -(-M // B)
+    Rref = fo.block_relevance(G.to_np(q), focus, fo.block_means(G.to_np(k), M, B))
+    for n_keep in (0, 1, 5, n_b):
+        fidx = G.i32(focus + [-1, -1, -1])
+        counts = G.i32([len(focus), 0])
+        scores, kept = G.gpu_block_scores(q, fidx, counts, k, None, M, B, n_keep)          # scans K
+        assert np.allclose(scores.cpu().numpy(), Rref, atol=1e-5)
+        assert kept.cpu().tolist() == fo.select_blocks(Rref, n_keep).tolist()
+        kbar = G.gpu_block_means(k, M, B)
+        scores2, kept2 = G.gpu_block_scores(q, fidx, counts, None, kbar, M, B, n_keep)     # cached means
+        assert torch.equal(scores, scores2) and torch.equal(kept, kept2)
+    # counts = NULL: every slot of focus_idx is used
+    scores3, _ = G.gpu_block_scores(q, G.i32(focus), None, k, None, M, B, 3)
+    assert np.allclose(scores3.cpu().numpy(), Rref, atol=1e-5)
+
+
+def test_top_c_ties_go_to_the_lower_block(G):
+    # integer-valued kbar and a one-hot query make R exact, so ties are exact ties
+    H, d, B, n_b, n_gen = 2, 64, 32, 300, 4
+    M = n_b * B
+    vals = np.random.default_rng(5).integers(0, 5, n_b).astype(np.float32)
+    k = torch.zeros(H, M + 8, d)
+    k[:, :M, 0] = torch.from_numpy(np.repeat(vals, B))
+    q = torch.zeros(H, n_gen, d)
+    q[:, :, 0] = 1.0
+    q, k = q.to(torch.bfloat16).to(G.DEV), k.to(torch.bfloat16).to(G.DEV)
+    for n_keep in (1, 7, 150, 299, 300):
+        scores, kept = G.gpu_block_scores(q, G.i32([0, 2]), None, k, None, M, B, n_keep)
+        assert np.array_equal(scores.cpu().numpy(), vals)
+        assert kept.cpu().tolist() == fo.top_indices(vals, n_keep).tolist()
+
+
+# ------------------------------------------------------------------------------------------------ stage 2b
+@pytest.mark.parametrize("H,M,N,d,n_gen,n_act,n_sink", [(2, 300, 20, 64, 16, 5, 3), (4, 1000, 40, 128, 40, 16, 10),
+                                                        (3, 2050, 33, 128, 80, 72, 20), (2, 4096, 0, 64, 32, 17, 41)])
+def test_find_sinks(G, H, M, N, d, n_gen, n_act, n_sink):
+    q, k = _rand_bf16(6, H, n_gen, d).to(G.DEV), _rand_bf16(7, H, M + N, d).to(G.DEV)
+    act = np.sort(np.random.default_rng(8).choice(n_gen, n_act, replace=False))
+    Sref = fo.sink_scores(G.to_np(q), act, G.to_np(k))
+    cap = n_act + 3
+    active = G.i32(list(act) + [-1] * (cap - n_act))
+    col, sinks = G.gpu_find_sinks(q, active, G.i32([0, n_act]), k, M, 64, n_sink)
+    S = col.cpu().numpy().astype(np.float64)
+    assert np.allclose(S, Sref, rtol=2e-4, atol=1e-9)
+    assert S.sum() == pytest.approx(1.0, abs=1e-4)
+    margin = fo.decision_margin(Sref, n_sink, np.arange(M + N) < M)
+    assert margin > 1e-5, "test inputs produce a near-tie; pick another seed"
+    assert sinks.cpu().tolist() == fo.select_sinks(Sref, M, n_sink).tolist()
+    # counts = NULL with an exact-size list gives the same answer
+    col2, sinks2 = G.gpu_find_sinks(q, G.i32(list(act)), None, k, M, 64, n_sink)
+    assert torch.equal(sinks, sinks2) and np.allclose(col2.cpu().numpy(), S, rtol=1e-6)
+
+
+def test_find_sinks_equal_keys_fall_back_to_lowest_positions(G):
+    H, M, N, d = 2, 500, 12, 64
+    k = _rand_bf16(9, 1, 1, d).expand(H, M + N, d).contiguous().to(G.DEV)
+    q = _rand_bf16(10, H, 16, d).to(G.DEV)
+    col, sinks = G.gpu_find_sinks(q, G.i32([0, 3, 8]), None, k, M, 64, 5)
+    assert np.allclose(col.cpu().numpy(), 1.0 / (M + N), rtol=1e-5)
+    # all column masses are equal only up to rounding on the device, so check the tie rule on exact values instead
+    assert len(set(sinks.cpu().tolist())) == 5
+
+
+# ------------------------------------------------------------------------------------------------ stage 3
+def _attn_case(G, H, M, N, d, B, n_gen, active, kept, sinks, seed=11, counts=None, cap=None):
+    q, k, v = (_rand_bf16(seed + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    cap = cap or len(active)
+    a_dev = G.i32(list(active) + [-1] * (cap - len(active)))
+    out, lse = G.gpu_sparse_attn(q, a_dev, counts, k, v, M, B, G.i32(kept) if len(kept) else None,
+                                 G.i32(sinks) if len(sinks) else None)
+    I_p = fo.attention_index_set(sinks, kept, M, B)
+    ref, ref_lse = fo.sparse_attention(G.to_np(q), active, G.to_np(k), G.to_np(v), I_p, M)
+    return out, lse, ref, ref_lse
+
+
+@pytest.mark.parametrize("H,M,N,d,B,n_gen,n_act,n_keep,n_sink", [
+    (4, 1024, 32, 64, 64, 32, 8, 4, 2),        # the tiny configuration's shape
+    (2, 1000, 37, 128, 48, 40, 16, 5, 3),      # ragged everything: M % B, B % 32, N % 32
+    (3, 2048, 64, 128, 128, 64, 16, 6, 4),
+    (2, 4096, 96, 128, 64, 128, 72, 20, 41),   # five query tiles (window-expanded queries), many sinks
+    (2, 600, 0, 64, 100, 24, 24, 2, 0),        # no response rows, no sinks
+    (1, 512, 16, 128, 128, 16, 1, 0, 1),       # a single query, no blocks
+    (5, 300, 5, 64, 7, 33, 33, 11, 9),         # tiny blocks
+])
+def test_sparse_attn(G, H, M, N, d, B, n_gen, n_act, n_keep, n_sink):
+    rng = np.random.default_rng(H * 1000 + M)
+    n_b = -(-M // B)
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    kept = rng.choice(n_b, n_keep, replace=False)        # unsorted on purpose
+    sinks = rng.choice(M, n_sink, replace=False)
+    out, lse, ref, ref_lse = _attn_case(G, H, M, N, d, B, n_gen, active, kept, sinks)
+    G.assert_attention_close(out, ref)
+    assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
+
+
+def test_sparse_attn_dense_reduction(G):
+    # keep every block, every row a query: plain bidirectional attention over all M+N keys
+    H, M, N, d, B, n_gen = 4, 3000, 72, 128, 128, 64
+    n_b = -(-M // B)
+    out, lse, ref, _ = _attn_case(G, H, M, N, d, B, n_gen, np.arange(n_gen), np.arange(n_b), [])
+    G.assert_attention_close(out, ref)
+    q, k, v = (_rand_bf16(11 + i, H, r, d).double() for i, r in enumerate((n_gen, M + N, M + N)))
+    sdpa = torch.nn.functional.scaled_dot_product_attention(q, k, v).numpy()
+    G.assert_attention_close(out, sdpa)
+
+
+def test_sparse_attn_union_is_a_set(G):
+    H, M, N, d, B, n_gen = 2, 1024, 32, 128, 64, 16
+    active = np.arange(16)
+    base = _attn_case(G, H, M, N, d, B, n_gen, active, [3, 9], [700, 5])[0]
+    # sinks inside kept blocks, repeated sinks, a repeated block, out-of-range entries and -1 padding change nothing
+    # (the split of the key axis differs with the list lengths, so equality holds up to the rounding of the merge)
+    same, _, ref, _ = _attn_case(G, H, M, N, d, B, n_gen, active, [3, 9, 3, -1, 16], [700, 5, 200, 600, 700, 5, -1, 5000])
+    G.assert_attention_close(same, ref)
+    assert (base.float() - same.float()).abs().max() <= 4e-3
+    # order of the lists is irrelevant
+    perm = _attn_case(G, H, M, N, d, B, n_gen, active, [9, 3], [5, 700])[0]
+    assert (base.float() - perm.float()).abs().max() <= 4e-3
+
+
+def test_sparse_attn_counts_and_untouched_rows(G):
+    H, M, N, d, B, n_gen = 2, 512, 32, 64, 64, 32
+    active = [1, 4, 6, 30, 31]
+    canary = torch.full((H, 8, d), 123.0, dtype=torch.bfloat16, device=G.DEV)
+    q, k, v = (_rand_bf16(21 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    a_dev = G.i32(active + [7, 7, 7])                      # slots past counts[1] must be ignored
+    out, lse = G.gpu_sparse_attn(q, a_dev, G.i32([0, 5]), k, v, M, B, G.i32([0, 5]), G.i32([100]), out=canary)
+    I_p = fo.attention_index_set([100], [0, 5], M, B)
+    ref, _ = fo.sparse_attention(G.to_np(q), active, G.to_np(k), G.to_np(v), I_p, M)
+    G.assert_attention_close(out[:, :5], ref)
+    assert (out[:, 5:] == 123.0).all()
+
+
+def test_sparse_attn_empty_key_set(G):
+    H, M, d = 2, 256, 64
+    q, k, v = (_rand_bf16(31 + i, H, r, d).to(G.DEV) for i, r in enumerate((8, M, M)))
+    out, lse = G.gpu_sparse_attn(q, G.i32([0, 1, 2]), None, k, v, M, 64, None, G.i32([-1, 9999]))
+    assert (out == 0).all() and torch.isinf(lse).all() and (lse < 0).all()
+
+
+def test_sparse_attn_single_key_returns_that_value_row(G):
+    H, M, d = 2, 256, 128
+    q, k, v = (_rand_bf16(41 + i, H, r, d).to(G.DEV) for i, r in enumerate((8, M, M)))
+    out, _ = G.gpu_sparse_attn(q, G.i32([3, 5]), None, k, v, M, 64, None, G.i32([77]))
+    assert torch.equal(out[:, 0], v[:, 77]) and torch.equal(out[:, 1], v[:, 77])
+
+
+def test_sparse_attn_is_deterministic_and_linear_in_v(G):
+    H, M, N, d, B, n_gen = 4, 2048, 64, 128, 128, 64
+    q, k, v = (_rand_bf16(51 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    args = (G.i32(np.arange(0, 64, 4)), None, k)
+    o1, _ = G.gpu_sparse_attn(q, *args, v, M, B, G.i32([1, 7, 8]), G.i32([900, 1500]))
+    o2, _ = G.gpu_sparse_attn(q, *args, v, M, B, G.i32([1, 7, 8]), G.i32([900, 1500]))
+    assert torch.equal(o1, o2)
+    o3, _ = G.gpu_sparse_attn(q, *args, (v.float() * 2).to(torch.bfloat16), M, B, G.i32([1, 7, 8]), G.i32([900, 1500]))
+    assert torch.equal(o3.float(), o1.float() * 2)         # scaling by two is exact in bf16
+
+
+# ------------------------------------------------------------------------------------------------ whole layer on the workloads
+@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx16k", "ctx32k"])
+def test_workload_layer_end_to_end(G, name):
+    w = fi.WORKLOADS[name]
+    q, k, v = (t.to(G.DEV) for t in fi.layer_qkv(w, 0))
+    conf = fi.confidence(w)
+    Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
+    # oracle
+    focus_ref = fo.select_focus(conf.numpy(), None, w.k_focus)
+    active_ref = fo.expand_window(focus_ref, w.window, 0, w.n_gen)
+    S_ref = fo.sink_scores(Q, active_ref, K)
+    sinks_ref = fo.select_sinks(S_ref, w.n_ctx, w.n_sink)
+    lay = fo.focus_layer(Q, K, V, focus_ref, active_ref, sinks_ref, w.n_ctx, w.block, w.n_keep)
+    assert fo.decision_margin(S_ref, w.n_sink, np.arange(w.n_kv) < w.n_ctx) > 1e-4
+    assert fo.decision_margin(lay["R"], w.n_keep) > 1e-4
+    # device, chained without host round trips of the index sets
+    focus, active, counts = G.gpu_select(conf.numpy(), fi.masked_all(w).numpy(), w.k_focus, w.window, 0, w.n_gen)
+    col, sinks = G.gpu_find_sinks(q, active, counts, k, w.n_ctx, w.block, w.n_sink)
+    scores, kept = G.gpu_block_scores(q, focus, counts, k, None, w.n_ctx, w.block, w.n_keep)
+    out, lse = G.gpu_sparse_attn(q, active, counts, k, v, w.n_ctx, w.block, kept, sinks)
+    assert focus.cpu().tolist() == focus_ref.tolist()
+    assert active.cpu().tolist() == active_ref.tolist()
+    assert sinks.cpu().tolist() == sinks_ref.tolist()
+    assert kept.cpu().tolist() == lay["blocks"].tolist()
+    assert np.allclose(col.cpu().numpy(), S_ref, rtol=2e-4, atol=1e-10)
+    assert np.allclose(scores.cpu().numpy(), lay["R"], atol=2e-6)
+    G.assert_attention_close(out, lay["out"])
+    assert np.allclose(lse.cpu().numpy(), lay["lse"], atol=2e-3)
+    # dense comparison baseline through the same entry point: every block kept
+    n_b = w.n_blocks
+    dense, _ = G.gpu_sparse_attn(q, active, counts, k, v, w.n_ctx, w.block, G.i32(np.arange(n_b)), None)
+    I_all = fo.attention_index_set([], np.arange(n_b), w.n_ctx, w.block)
+    G.assert_attention_close(dense, fo.sparse_attention(Q, active_ref, K, V, I_all, w.n_ctx)[0])
+
+
+def test_stack_reuses_probe_layer_sinks(G):
+    # a short stack shaped like the tiny workload: sinks found at layer 1 are handed, as the same device buffer, to layers 2..4
+    w = fi.strong_sinks(fi.TINY).with_(n_layers=5, probe_layer=1, first_sparse_layer=2)
+    conf = fi.confidence(w)
+    tensors = {l: tuple(t.to(G.DEV) for t in fi.layer_qkv(w, l)) for l in range(w.n_layers)}
+    step = fo.focus_step(conf.numpy(), None, w.k_focus, w.window, 0, w.n_gen,
+                         lambda l: tuple(G.to_np(t) for t in tensors[l]), w.probe_layer, range(2, 5), w.n_ctx, w.block,
+                         w.n_keep, w.n_sink)
+    assert step["sinks"].tolist() == list(w.sink_positions)          # the planted keys are the sinks
+    focus, active, counts = G.gpu_select(conf.numpy(), None, w.k_focus, w.window, 0, w.n_gen)
+    qp, kp, _ = tensors[w.probe_layer]
+    _, sinks = G.gpu_find_sinks(qp, active, counts, kp, w.n_ctx, w.block, w.n_sink)
+    frozen = sinks.clone()
+    assert sinks.cpu().tolist() == step["sinks"].tolist()
+    for l in range(2, 5):
+        q, k, v = tensors[l]
+        _, kept = G.gpu_block_scores(q, focus, counts, k, None, w.n_ctx, w.block, w.n_keep)
+        out, _ = G.gpu_sparse_attn(q, active, counts, k, v, w.n_ctx, w.block, kept, sinks)
+        assert torch.equal(sinks, frozen)                              # reused unchanged
+        assert kept.cpu().tolist() == step["layers"][l]["blocks"].tolist()
+        G.assert_attention_close(out, step["layers"][l]["out"])
