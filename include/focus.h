@@ -126,8 +126,9 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
 
 /*
  * Sink-aware sparse attention (Sec. 5.3, Eq. 8 and Eq. 9).
- *   I_p  = I_sink  united with  all rows of the kept blocks          (a set: a sink inside a kept block, a
- *          repeated entry, and entries < 0 or outside the prompt are attended once / ignored)
+ *   I_p  = I_sink  united with  all rows of the kept blocks          (a set: a sink inside a kept block or listed
+ *          twice is attended once; sink entries < 0 or >= M and block ids < 0 or >= n_b are ignored; the block
+ *          list itself must not repeat a block — B_relevant is a set, and Top-C never repeats one)
  *   out[h, a, :] = softmax_j(Q[h, i_a] . K[h, j] / sqrt(d)) . V[h, j, :],  j over I_p and the N response rows,
  *          for the a-th active query i_a; bidirectional, no mask.
  *   kept_blocks [dev] int32[n_keep], sink_idx [dev] int32[n_sink] (either may be NULL when its count is 0)

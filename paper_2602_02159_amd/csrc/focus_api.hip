@@ -85,9 +85,17 @@ static int check_shape(const focus_shape* s, bool need_q, bool need_k, bool need
   return FOCUS_OK;
 }
 
-static size_t ws_block_scores(const focus_shape& s) {
+struct ScoreWs {
+  size_t kbar, part, scores, total;
+};
+static ScoreWs ws_block_scores(const focus_shape& s) {
   const size_t n_b = ceil_div(s.n_ctx, s.block);
-  return align_up((size_t)s.n_heads * n_b * s.head_dim * sizeof(float)) + align_up(n_b * sizeof(float));
+  ScoreWs w;
+  w.kbar = 0;
+  w.part = align_up((size_t)s.n_heads * n_b * s.head_dim * sizeof(float));
+  w.scores = w.part + align_up((size_t)s.n_heads * n_b * sizeof(float));
+  w.total = w.scores + align_up(n_b * sizeof(float));
+  return w;
 }
 
 struct SinkWs {
@@ -139,7 +147,7 @@ size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_a
   const int n_b = ceil_div(shape->n_ctx, shape->block);
   switch (fn) {
     case FOCUS_FN_BLOCK_SCORES:
-      return ws_block_scores(*shape);
+      return ws_block_scores(*shape).total;
     case FOCUS_FN_FIND_SINKS:
       if (max_active < 1 || max_active > shape->n_gen) return 0;
       return ws_find_sinks(*shape, plan_logits(*shape, max_active)).total;
@@ -192,25 +200,24 @@ int focus_block_scores(const void* Q, const int32_t* focus_idx, const int32_t* c
   if (n_keep > 0 && !kept_blocks) return fail(FOCUS_EINVAL, "focus_block_scores: kept_blocks is NULL");
   if (!aligned16(Q) || (kbar && !aligned16(kbar)) || (!kbar && !aligned16(K)))
     return fail(FOCUS_EINVAL, "focus_block_scores: pointers must be 16-byte aligned");
-  if (!workspace || ws_bytes < ws_block_scores(*shape) || !aligned16(workspace))
-    return fail(FOCUS_EWORKSPACE, "focus_block_scores: workspace needs %zu bytes, 16-byte aligned", ws_block_scores(*shape));
+  const ScoreWs w = ws_block_scores(*shape);
+  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "focus_block_scores: workspace needs %zu bytes, 16-byte aligned", w.total);
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  float* ws_kbar = reinterpret_cast<float*>(ws);
-  float* ws_scores = reinterpret_cast<float*>(ws + align_up((size_t)shape->n_heads * n_b * shape->head_dim * sizeof(float)));
+  float* ws_kbar = reinterpret_cast<float*>(ws + w.kbar);
+  float* part = reinterpret_cast<float*>(ws + w.part);
+  float* R = scores ? scores : reinterpret_cast<float*>(ws + w.scores);
   hipError_t e;
   if (!kbar) {
     e = launch_block_means(K, *shape, ws_kbar, st);
     if (e != hipSuccess) return launch_fail("focus_block_scores(block means)", e);
     kbar = ws_kbar;
   }
-  float* R = scores ? scores : ws_scores;
-  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, R, st);
+  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
   if (e != hipSuccess) return launch_fail("focus_block_scores(relevance)", e);
-  if (n_keep > 0) {
-    e = launch_topk(R, n_b, n_keep, kept_blocks, st);
-    if (e != hipSuccess) return launch_fail("focus_block_scores(top-C)", e);
-  }
+  e = launch_reduce_topk(part, shape->n_heads, counts, n_focus_max, R, n_b, n_keep, kept_blocks, st);
+  if (e != hipSuccess) return launch_fail("focus_block_scores(top-C)", e);
   return FOCUS_OK;
 }
 
@@ -241,7 +248,7 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   e = launch_column_mass(logits, lse2, counts, max_active, shape->n_heads, L, p.q_pad, S, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
   if (n_sink > 0) {
-    e = launch_topk(S, shape->n_ctx, n_sink, sink_idx, st);
+    e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N)", e);
   }
   return FOCUS_OK;

@@ -73,4 +73,23 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
   return base + incl - v;
 }
 
+// Workgroup exclusive prefix COUNT of one flag per thread, from wavefront ballots: one LDS write, one barrier
+// pair and at most blockDim/64 LDS reads per thread.  `wsum` is shared memory of at least 2 * (blockDim/64)
+// words.  Every thread of the workgroup must call it.
+__device__ __forceinline__ uint32_t block_flag_scan(bool flag, uint32_t* wsum, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  const unsigned long long b = __ballot(flag);
+  __syncthreads();  // wsum may still be read from a previous call
+  if (lane == 0) wsum[wid] = (uint32_t)__popcll(b);
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    const uint32_t s = wsum[w];
+    if (w < wid) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + (uint32_t)__popcll(b & ((1ull << lane) - 1ull));
+}
+
 }  // namespace focus

@@ -33,10 +33,13 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
                                  int hi, int32_t* focus_idx, int32_t* active_idx, int max_active, int32_t* counts,
                                  hipStream_t st);
 hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, hipStream_t st);
+// per-head partial relevances part[H, n_b] (sum over the focus queries, not yet scaled)
 hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const int32_t* counts, int n_focus_max,
-                                  const float* kbar, const focus_shape& s, float* scores, hipStream_t st);
+                                  const float* kbar, const focus_shape& s, float* part, hipStream_t st);
+// values[j] = sum_h part[h, j] / (|I_focus| n_parts) when part != nullptr (else values are read), then
 // top-k over values[0..n): out[k] ascending indices
-hipError_t launch_topk(const float* values, int n, int k, int32_t* out, hipStream_t st);
+hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* counts, int n_focus_max, float* values, int n,
+                              int k, int32_t* out, hipStream_t st);
 hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_split, float* lse2, hipStream_t st);
 hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active,
                               int H, int L, int q_pad, float* col_mass, hipStream_t st);

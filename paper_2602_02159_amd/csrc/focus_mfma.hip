@@ -6,23 +6,38 @@
 //                       probe layer, plus per-split row maxima / sums for the softmax normaliser.
 //
 // Work decomposition.  The key axis of one head is cut into sub-tiles of 32 rows.  A wavefront owns a sub-tile
-// from the global load to the MFMAs: it reads the 32 K rows (and V rows) with wave-wide, fully coalesced
-// 16-byte loads (1 KB of consecutive bytes per instruction), stages them in its private slice of LDS with an
-// XOR swizzle, and reads them back in MFMA operand layout.  Wavefronts never wait for each other inside the
-// key loop; the four wavefronts of a workgroup meet once, at the end, to merge their softmax states into one
-// partial result per workgroup.
+// from the memory request to the MFMAs: the 32 K rows (and V rows) go from HBM straight into the wavefront's
+// private slice of LDS (global_load_lds_dwordx4: no staging registers, no ds_write), 1 KB of consecutive bytes
+// per instruction, with an XOR swizzle applied on the global side so that the operand reads are conflict free.
+// Wavefronts never wait for each other inside the key loop; the four wavefronts of a workgroup meet once, at
+// the end, to merge their softmax states into one partial result per workgroup.  Loads of one wavefront overlap
+// with the MFMAs of the others (two workgroups = eight wavefronts per CU).
 //
 // MFMA layout used (16x16x32, D[i][j] += sum_k A[i][k] B[k][j]; lane = 16*g + c):
 //   A operand: lane holds A[i = c][k = 8g .. 8g+7];  B operand: lane holds B[k = 8g .. 8g+7][j = c];
 //   D: lane holds D[i = 4g + r][j = c], r = 0..3.
 // Logits are produced transposed, S^T[key][query] = K_tile . Q^T, so that every lane keeps the values of ONE
-// query (j = c): row maxima, sums and rescale factors are lane-local up to two cross-lane shuffles, and the
+// query (j = c): row maxima, sums and rescale factors are lane-local up to two lane swaps, and the
 // exponentiated values already sit in B-operand layout for the second product O^T[dcol][query] = V^T . P^T,
 // where the contraction slot (g, e) stands for key 16*(e/4) + 4g + (e%4) of the sub-tile on both operands.
+// The V^T operand is read from the row-major staged tile with the transposing LDS read ds_read_b64_tr_b16.
 #include "focus_common.h"
 #include "focus_kernels.h"
 
 namespace focus {
+
+// Optional per-wave phase stamps for kernel tuning (never defined in the shipped build).
+#ifdef FOCUS_STAMPS
+__device__ long long* g_stamps;
+#define FOCUS_STAMP(i)                                                                                          \
+  do {                                                                                                          \
+    if ((threadIdx.x & 63) == 0)                                                                                \
+      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = \
+          (i) == 0 ? wall_clock64() : clock64();                                                                \
+  } while (0)
+#else
+#define FOCUS_STAMP(i)
+#endif
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -38,13 +53,16 @@ struct Geo {
   static constexpr int kStageBytes = kSubTile * kRowBytes;  // one staged K (or V) sub-tile
 };
 
-// byte offset of 16-byte chunk `chunk` of staged row `row` (XOR swizzle keeps both the row-major writes and the
-// operand-layout reads spread over all banks)
+// byte offset of 16-byte chunk `chunk` of staged row `row`: position chunk ^ (row mod chunks-per-row)
 template <int D>
 __device__ __forceinline__ int stage_off(int row, int chunk) {
   return row * Geo<D>::kRowBytes + ((chunk ^ (row & (Geo<D>::kChunks - 1))) << 4);
 }
 
+// s_waitcnt vmcnt(0): every outstanding global load, LDS-direct ones included, has landed
+__device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// ---------------------------------------------------------------------------------------- sub-tiles
 // Which rows of K/V a sub-tile covers.  Wave-uniform.
 struct SubTile {
   int row0;        // first row when contiguous (kind 0), first sink entry when kind 1
@@ -52,12 +70,16 @@ struct SubTile {
   uint32_t vmask;  // bit s set: slot s holds a key that takes part
 };
 
-// Resolve sub-tile `st` of the attention key list: kept blocks first (n_keep * sub_per_block sub-tiles), then
-// the response rows, then the sinks.  The union of Eq. 8 is a set: a block listed twice is taken the first
-// time only; a sink is dropped when it is outside the prompt, inside a kept block or listed earlier.
-__device__ __forceinline__ SubTile resolve_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
-                                                   const int32_t* __restrict__ kept_blocks, int n_keep,
-                                                   const int32_t* __restrict__ sink_idx, int n_sink) {
+__device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xffffffffu : (n > 0 ? ((1u << n) - 1u) : 0u); }
+
+// Locate sub-tile `st` of the attention key list: kept blocks first (n_keep * sub_per_block sub-tiles), then
+// the response rows, then the sinks.  Block ids outside [0, n_b) are skipped.  The union of Eq. 8 is a set:
+// a sink is dropped when it is outside the prompt, inside a kept block or listed earlier in sink_idx (the block
+// list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r and the two index lists are
+// scanned 64 entries per load.
+__device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
+                                                  const int32_t* __restrict__ kept_blocks, int n_keep,
+                                                  const int32_t* __restrict__ sink_idx, int n_sink) {
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
@@ -68,92 +90,108 @@ __device__ __forceinline__ SubTile resolve_subtile(int st, int lane, int M, int 
     const int slot = st / sub_per_block, sub = st % sub_per_block;
     const int b = kept_blocks[slot];
     if (b < 0 || b >= n_b) return t;
-    bool dup = false;
-    for (int s = lane; s < slot; s += kWave) dup |= (kept_blocks[s] == b);
-    if (__ballot(dup) != 0ull) return t;
     const int first = b * B + sub * kSubTile;
     const int end = min(min((b + 1) * B, M), first + kSubTile);
-    const int n = end - first;
     t.row0 = first;
-    t.vmask = n >= 32 ? 0xffffffffu : (n > 0 ? ((1u << n) - 1u) : 0u);
+    t.vmask = low_mask(end - first);
     return t;
   }
   st -= n_blk_sub;
   if (st < n_resp_sub) {
     const int first = M + st * kSubTile;
-    const int n = min(M + N - first, kSubTile);
     t.row0 = first;
-    t.vmask = n >= 32 ? 0xffffffffu : (n > 0 ? ((1u << n) - 1u) : 0u);
+    t.vmask = low_mask(min(M + N - first, kSubTile));
     return t;
   }
   st -= n_resp_sub;
   t.kind = 1;
   t.row0 = st * kSubTile;
-  bool ok = false;
   const int e = t.row0 + lane;
-  if (lane < kSubTile && e < n_sink) {
-    const int s = sink_idx[e];
-    ok = s >= 0 && s < M;
-    if (ok) {
-      const int sb = s / B;
-      for (int j = 0; j < n_keep && ok; ++j) ok = kept_blocks[j] != sb;
-      for (int j = 0; j < e && ok; ++j) ok = sink_idx[j] != s;
+  const int mine = (lane < kSubTile && e < n_sink) ? sink_idx[e] : -1;
+  const bool in_prompt = mine >= 0 && mine < M;
+  const int my_block = in_prompt ? mine / B : -1;
+  uint32_t bad = 0u;
+  for (int j0 = 0; j0 < n_keep; j0 += kWave) {
+    const int v = j0 + lane < n_keep ? kept_blocks[j0 + lane] : -2;
+#pragma unroll 4
+    for (int r = 0; r < kSubTile; ++r) {
+      const int sb = __shfl(my_block, r, kWave);
+      if (__ballot(v == sb) != 0ull) bad |= 1u << r;
     }
   }
-  t.vmask = (uint32_t)(__ballot(ok) & 0xffffffffull);
+  const int e_end = min(t.row0 + kSubTile, n_sink);
+  for (int j0 = 0; j0 < e_end; j0 += kWave) {
+    const int idx = j0 + lane;
+    const int v = idx < e_end ? sink_idx[idx] : -2;
+#pragma unroll 4
+    for (int r = 0; r < kSubTile; ++r) {
+      const int s = __shfl(mine, r, kWave);
+      if (__ballot(v == s && idx < t.row0 + r) != 0ull) bad |= 1u << r;
+    }
+  }
+  t.vmask = (uint32_t)(__ballot(in_prompt) & 0xffffffffull) & ~bad;
   return t;
 }
 
-// Source row of staged slot `slot` (only meaningful when its vmask bit is set).
-__device__ __forceinline__ int slot_row(const SubTile& t, int slot, const int32_t* __restrict__ sink_idx) {
-  return t.kind == 0 ? t.row0 + slot : sink_idx[t.row0 + slot];
-}
-
-// Wave-wide coalesced load of one 32-row sub-tile of a [rows, D] bf16 matrix into registers.
+// HBM -> LDS for one 32-row sub-tile of a [rows, D] bf16 matrix.  Lane l of load i supplies the 16 bytes that
+// land at stage + 1024 i + 16 l, i.e. position (l mod chunks) of staged row i * rows_per_load + l / chunks; with
+// the swizzle that position holds logical chunk (l mod chunks) ^ (row mod chunks).  No load is predicated: a
+// slot that holds no key reads a valid row instead (the last valid row of a contiguous tile, row 0 for a
+// dropped sink) and is masked out of the softmax.  Requires t.vmask != 0.
 template <int D>
-__device__ __forceinline__ void load_subtile(uint4 (&r)[Geo<D>::kLoads], const uint16_t* __restrict__ base, int64_t sn,
-                                             const SubTile& t, const int32_t* __restrict__ sink_idx, int lane) {
-  constexpr int C = Geo<D>::kChunks;
+__device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
+                                              const int32_t* __restrict__ sink_idx, int n_sink, char* stage, int lane) {
+  using G = Geo<D>;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
+  const int last = 31 - __builtin_clz(t.vmask);
 #pragma unroll
-  for (int i = 0; i < Geo<D>::kLoads; ++i) {
-    const int slot = i * Geo<D>::kRowsPerLoad + lane / C;
-    if ((t.vmask >> slot) & 1u) {
-      const int row = slot_row(t, slot, sink_idx);
-      r[i] = *reinterpret_cast<const uint4*>(base + (int64_t)row * sn + (lane % C) * 8);
-    } else {
-      r[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (int i = 0; i < G::kLoads; ++i) {
+    const int slot = i * G::kRowsPerLoad + sub;
+    int row = t.row0 + min(slot, last);
+    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
+      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
+      row = ((t.vmask >> slot) & 1u) ? s : 0;
     }
+    const int chunk = pos ^ (slot & (G::kChunks - 1));
+    const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, 0);
   }
 }
 
-template <int D>
-__device__ __forceinline__ void stage_subtile(char* stage, const uint4 (&r)[Geo<D>::kLoads], int lane) {
-  constexpr int C = Geo<D>::kChunks;
-#pragma unroll
-  for (int i = 0; i < Geo<D>::kLoads; ++i) {
-    const int slot = i * Geo<D>::kRowsPerLoad + lane / C;
-    *reinterpret_cast<uint4*>(stage + stage_off<D>(slot, lane % C)) = r[i];
-  }
+// ---------------------------------------------------------------------------------------- queries
+// Row of Q for query slot q0 + (lane % 16), or -1.  The index is fetched for every slot below max_active
+// without waiting for the device-side count; slots at or past the count are zeroed afterwards (mask_q_tile),
+// which keeps the count out of the load chain.
+__device__ __forceinline__ int fetch_q_row(const int32_t* __restrict__ active_idx, int q0, int max_active, int n_gen,
+                                           int lane) {
+  const int a = q0 + (lane & 15);
+  int row = -1;
+  if (a < max_active) row = active_idx[a];
+  return (row >= 0 && row < n_gen) ? row : -1;
 }
-
 // Q rows of one 16-query tile in B-operand layout: lane (c, g) holds Q[query c][32*kk + 8g .. +7].
 template <int D>
 __device__ __forceinline__ void load_q_tile(bf16x8 (&q)[Geo<D>::kKSteps], const uint16_t* __restrict__ Qh, int64_t qsn,
-                                            const int32_t* __restrict__ active_idx, int q0, int n_act, int n_gen,
-                                            int lane) {
-  const int c = lane & 15, g = lane >> 4;
-  const int a = q0 + c;
-  int row = -1;
-  if (a < n_act) row = active_idx[a];
-  const bool ok = row >= 0 && row < n_gen;
+                                            int row, int lane) {
+  const int g = lane >> 4;
+  const uint16_t* src = Qh + (int64_t)max(row, 0) * qsn + g * 8;
 #pragma unroll
   for (int kk = 0; kk < Geo<D>::kKSteps; ++kk) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (ok) v = *reinterpret_cast<const uint4*>(Qh + (int64_t)row * qsn + kk * 32 + g * 8);
-    q[kk] = as_bf16x8(v);
+    const uint4 v = *reinterpret_cast<const uint4*>(src + kk * 32);
+    q[kk] = as_bf16x8(row >= 0 ? v : make_uint4(0u, 0u, 0u, 0u));
+  }
+}
+template <int D>
+__device__ __forceinline__ void mask_q_tile(bf16x8 (&q)[Geo<D>::kKSteps], int q0, int n_act, int lane) {
+  if (q0 + (lane & 15) >= n_act) {
+#pragma unroll
+    for (int kk = 0; kk < Geo<D>::kKSteps; ++kk) q[kk] = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
   }
 }
 
+// ---------------------------------------------------------------------------------------- tile math
 // S^T tiles of one staged K sub-tile against NQT query tiles: acc[qt][kt][r] = logit of key 16kt + 4g + r.
 template <int D, int NQT>
 __device__ __forceinline__ void qk_subtile(floatx4 (&acc)[NQT][2], const char* stageK,
@@ -173,13 +211,79 @@ __device__ __forceinline__ void qk_subtile(floatx4 (&acc)[NQT][2], const char* s
   }
 }
 
-__device__ __forceinline__ float group_max(float v) {  // over the 4 lanes that share a query (lane % 16)
-  v = fmaxf(v, __shfl_xor(v, 16, kWave));
-  return fmaxf(v, __shfl_xor(v, 32, kWave));
+// Reductions over the 4 lanes that share a query (lane % 16), via v_permlane32_swap / v_permlane16_swap:
+// swap(x, x) returns {value of the partner in the even half/row, value of the partner in the odd half/row}.
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float group_max(float v) {
+  uintx2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+  uintx2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
 }
 __device__ __forceinline__ float group_sum(float v) {
-  v += __shfl_xor(v, 16, kWave);
-  return v + __shfl_xor(v, 32, kWave);
+  uintx2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a.x) + __uint_as_float(a.y);
+  uintx2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+
+// eight fp32 -> eight bf16 (round to nearest even) with v_cvt_pk_bf16_f32
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((floatx2){lo, hi}, bf16x2));
+}
+__device__ __forceinline__ bf16x8 pack_bf16x8(const float (&v)[8]) {
+  return as_bf16x8(make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]), cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7])));
+}
+
+// A operand of the PV product for d-column tile `ct`: lane (c, g) needs V[key slot (g, e)][16 ct + c], e = 0..7,
+// i.e. eight different rows at one column of the row-major staged tile.  ds_read_b64_tr_b16 does that
+// transposition in the LDS unit: within a block of 16 lanes, lane i receives element (i % 4) of the 8-byte
+// groups addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  Lane s therefore points at row 4g + s/4 (first
+// read) or 16 + 4g + s/4 (second read), columns 16 ct + 4 (s % 4) .. + 3.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+template <int D>
+__device__ __forceinline__ bf16x8 read_v_operand(const char* stageV, int ct, int lane) {
+  const int s = lane & 15, g = lane >> 4;
+  const int row = 4 * g + (s >> 2);
+  const int col = 16 * ct + 4 * (s & 3);
+  const int off0 = stage_off<D>(row, col >> 3) + (col & 7) * 2;
+  const int off1 = stage_off<D>(row + 16, col >> 3) + (col & 7) * 2;
+  typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
+  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stageV + off0));
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stageV + off1));
+  struct { shortx4 a, b; } both = {lo, hi};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+// One step of the base-2 online softmax for the 8 logits a lane holds of one query; returns the rescale factor
+// of the running state and leaves exp2(s - m) in ps.
+__device__ __forceinline__ float softmax_step(const floatx4 (&acc)[2], uint32_t vmask, int g, float scale_log2, float& m_run,
+                                              float& l_run, float (&ps)[8]) {
+  float s[8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
+    const float v = acc[e >> 2][e & 3] * scale_log2;
+    s[e] = ((vmask >> slot) & 1u) ? v : -INFINITY;
+    mx = fmaxf(mx, s[e]);
+  }
+  mx = group_max(mx);
+  const float m_new = fmaxf(m_run, mx);
+  const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+  float lsum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    ps[e] = __builtin_amdgcn_exp2f(s[e] - m_use);
+    lsum += ps[e];
+  }
+  lsum = group_sum(lsum);
+  l_run = l_run * alpha + lsum;
+  m_run = m_new;
+  return alpha;
 }
 
 // =====================================================================================================
@@ -204,28 +308,51 @@ struct AttnArgs {
 };
 
 template <int D, int NQT>
-__global__ __launch_bounds__(256) void sparse_attn_kernel(const AttnArgs p) {
+__global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
   using G = Geo<D>;
   constexpr int kWaveLds = 2 * G::kStageBytes;  // K stage + V stage, reused for the final merge
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * kWaveLds];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, h = blockIdx.y, qg = blockIdx.z;
-  const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
   const int q_base = qg * NQT * kQTile;
+  FOCUS_STAMP(0);
+  FOCUS_STAMP(1);
 
   char* stageK = lds + wave * kWaveLds;
   char* stageV = stageK + G::kStageBytes;
-
   const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
   const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
 
+  // Order of the memory requests: the query row ids first (tiny, they return first), then the first
+  // sub-tile's K and V rows as soon as its block id is known, then the query rows and the device-side count.
+  const int st_begin = split * p.per_split;
+  const int st_end = min(st_begin + p.per_split, p.n_sub);
+  int st = st_begin + wave;
+  int qrow[NQT];
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) qrow[qt] = fetch_q_row(p.active_idx, q_base + qt * kQTile, p.max_active, p.n_gen, lane);
+  SubTile t;
+  t.kind = 0;
+  t.row0 = 0;
+  t.vmask = 0u;
+  if (st < st_end) {
+    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, p.kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+    if (t.vmask != 0u) {
+      issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+      issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+    }
+  }
+  FOCUS_STAMP(2);
   bf16x8 q[NQT][G::kKSteps];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt)
-    load_q_tile<D>(q[qt], Qh, p.qsn, p.active_idx, q_base + qt * kQTile, n_act, p.n_gen, lane);
+  for (int qt = 0; qt < NQT; ++qt) load_q_tile<D>(q[qt], Qh, p.qsn, qrow[qt], lane);
+  const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) mask_q_tile<D>(q[qt], q_base + qt * kQTile, n_act, lane);
 
   float m_run[NQT], l_run[NQT];
   floatx4 o[NQT][G::kColTiles];
@@ -237,82 +364,53 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(const AttnArgs p) {
     for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  const int st_begin = split * p.per_split;
-  const int st_end = min(st_begin + p.per_split, p.n_sub);
-  for (int st = st_begin + wave; st < st_end; st += kWavesPerGroup) {
-    const SubTile t = resolve_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, p.kept_blocks, p.n_keep,
-                                      p.sink_idx, p.n_sink);
-    if (t.vmask == 0u) continue;
-    uint4 kr[G::kLoads], vr[G::kLoads];
-    load_subtile<D>(kr, Kh, p.ksn, t, p.sink_idx, lane);
-    load_subtile<D>(vr, Vh, p.vsn, t, p.sink_idx, lane);
-    stage_subtile<D>(stageK, kr, lane);
-    stage_subtile<D>(stageV, vr, lane);
-
-    floatx4 acc[NQT][2];
-    qk_subtile<D, NQT>(acc, stageK, q, lane);
-
-    // online softmax, base-2 domain; every lane works on query c
-    bf16x8 pb[NQT];
+  bool first = true;
+  while (st < st_end) {
+    const uint32_t vmask = t.vmask;
+    if (vmask != 0u) {
+      wait_loads();
+      FOCUS_STAMP(3);
+      floatx4 acc[NQT][2];
+      qk_subtile<D, NQT>(acc, stageK, q, lane);
+      FOCUS_STAMP(4);
+      bf16x8 pb[NQT];
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      float s[8];
-      float mx = -INFINITY;
+      for (int qt = 0; qt < NQT; ++qt) {
+        float ps[8];
+        const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
+        if (!first) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-        const float v = acc[qt][e >> 2][e & 3] * p.scale_log2;
-        s[e] = ((t.vmask >> slot) & 1u) ? v : -INFINITY;
-        mx = fmaxf(mx, s[e]);
+          for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
+        }
+        pb[qt] = pack_bf16x8(ps);
       }
-      mx = group_max(mx);  // vmask != 0, so mx is finite unless a logit is itself infinite
-      const float m_new = fmaxf(m_run[qt], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_use);
-      float ps[8];
-      float lsum = 0.f;
+      FOCUS_STAMP(5);
+      // O^T[dcol][query] += V^T . P^T
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        ps[e] = __builtin_amdgcn_exp2f(s[e] - m_use);
-        lsum += ps[e];
+      for (int ct = 0; ct < G::kColTiles; ++ct) {
+        const bf16x8 a = read_v_operand<D>(stageV, ct, lane);
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
       }
-      lsum = group_sum(lsum);
-      l_run[qt] = l_run[qt] * alpha + lsum;
-      m_run[qt] = m_new;
-#pragma unroll
-      for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
-      uint4 pk;
-      pk.x = pack_bf16x2(ps[0], ps[1]);
-      pk.y = pack_bf16x2(ps[2], ps[3]);
-      pk.z = pack_bf16x2(ps[4], ps[5]);
-      pk.w = pack_bf16x2(ps[6], ps[7]);
-      pb[qt] = as_bf16x8(pk);
+      first = false;
+      FOCUS_STAMP(6);
     }
-
-    // O^T[dcol][query] += V^T . P^T ; A operand gathered transposed from the staged V rows
-#pragma unroll
-    for (int ct = 0; ct < G::kColTiles; ++ct) {
-      const int col = ct * 16 + c;
-      uint32_t w[4];
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const int e = 2 * e2;
-        const int slot0 = 16 * (e >> 2) + 4 * g + (e & 3);
-        const uint32_t lo = *reinterpret_cast<const uint16_t*>(stageV + stage_off<D>(slot0, col >> 3) + (col & 7) * 2);
-        const uint32_t hi =
-            *reinterpret_cast<const uint16_t*>(stageV + stage_off<D>(slot0 + 1, col >> 3) + (col & 7) * 2);
-        w[e2] = lo | (hi << 16);
+    st += kWavesPerGroup;
+    if (st < st_end) {
+      t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, p.kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+      if (t.vmask != 0u) {
+        issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+        issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
       }
-      const bf16x8 a = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
     }
   }
+  FOCUS_STAMP(7);
 
   // ---- merge the four wavefronts, one query tile at a time, through each wave's own LDS slice
   float* myO = reinterpret_cast<float*>(stageK);               // [16][D]
   float* myML = reinterpret_cast<float*>(stageK + 16 * D * 4);  // [16][2]
   constexpr int kPerThread = D / 16;                            // output columns per thread in the merge
+  constexpr int kVec = kPerThread / 4;
   const int mq = threadIdx.x >> 4;                              // query of the tile this thread merges
   const int mc = (threadIdx.x & 15) * kPerThread;
 #pragma unroll
@@ -321,31 +419,33 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(const AttnArgs p) {
 #pragma unroll
     for (int ct = 0; ct < G::kColTiles; ++ct)
       *reinterpret_cast<floatx4*>(myO + c * D + ct * 16 + 4 * g) = o[qt][ct];
-    if (g == 0) {
-      myML[2 * c] = m_run[qt];
-      myML[2 * c + 1] = l_run[qt];
-    }
+    if (g == 0) *reinterpret_cast<float2*>(myML + 2 * c) = make_float2(m_run[qt], l_run[qt]);
     __syncthreads();
-    float mw[kWavesPerGroup], lw[kWavesPerGroup];
-    float mmax = -INFINITY;
+    float2 ml[kWavesPerGroup];
+    float4 ow[kWavesPerGroup][kVec];
 #pragma unroll
     for (int w = 0; w < kWavesPerGroup; ++w) {
-      const float* ml = reinterpret_cast<const float*>(lds + w * kWaveLds + 16 * D * 4);
-      mw[w] = ml[2 * mq];
-      lw[w] = ml[2 * mq + 1];
-      mmax = fmaxf(mmax, mw[w]);
+      const char* wbase = lds + w * kWaveLds;
+      ml[w] = *reinterpret_cast<const float2*>(wbase + 16 * D * 4 + 8 * mq);
+#pragma unroll
+      for (int i = 0; i < kVec; ++i) ow[w][i] = *reinterpret_cast<const float4*>(wbase + (mq * D + mc + 4 * i) * 4);
     }
+    float mmax = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
     float acc_o[kPerThread];
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) acc_o[i] = 0.f;
     float lsum = 0.f;
 #pragma unroll
     for (int w = 0; w < kWavesPerGroup; ++w) {
-      const float f = lw[w] > 0.f ? __builtin_amdgcn_exp2f(mw[w] - mmax) : 0.f;
-      lsum += f * lw[w];
-      const float* ow = reinterpret_cast<const float*>(lds + w * kWaveLds) + mq * D + mc;
+      const float f = ml[w].y > 0.f ? __builtin_amdgcn_exp2f(ml[w].x - mmax) : 0.f;
+      lsum += f * ml[w].y;
 #pragma unroll
-      for (int i = 0; i < kPerThread; ++i) acc_o[i] += f * ow[i];
+      for (int i = 0; i < kVec; ++i) {
+        acc_o[4 * i] += f * ow[w][i].x;
+        acc_o[4 * i + 1] += f * ow[w][i].y;
+        acc_o[4 * i + 2] += f * ow[w][i].z;
+        acc_o[4 * i + 3] += f * ow[w][i].w;
+      }
     }
     const int a = q_base + qt * kQTile + mq;  // position in the active list
     if (a < n_act) {
@@ -354,7 +454,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(const AttnArgs p) {
         uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)a * p.osn + mc;
 #pragma unroll
         for (int i = 0; i < kPerThread; i += 2)
-          *reinterpret_cast<uint32_t*>(dst + i) = pack_bf16x2(acc_o[i] * inv, acc_o[i + 1] * inv);
+          *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
         if (p.lse && (threadIdx.x & 15) == 0)
           p.lse[(int64_t)h * p.max_active + a] = lsum > 0.f ? (mmax + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
       } else {
@@ -363,17 +463,17 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(const AttnArgs p) {
 #pragma unroll
         for (int i = 0; i < kPerThread; i += 4)
           *reinterpret_cast<float4*>(dst + i) = make_float4(acc_o[i], acc_o[i + 1], acc_o[i + 2], acc_o[i + 3]);
-        if ((threadIdx.x & 15) == 0) {
-          p.part_ml[2 * row] = lsum > 0.f ? mmax : -INFINITY;
-          p.part_ml[2 * row + 1] = lsum;
-        }
+        if ((threadIdx.x & 15) == 0)
+          *reinterpret_cast<float2*>(p.part_ml + 2 * row) = make_float2(lsum > 0.f ? mmax : -INFINITY, lsum);
       }
     }
+    FOCUS_STAMP(8);
   }
 }
 
 // Merge of the per-split partial results: out = sum_s f_s O_s / sum_s f_s l_s, f_s = exp2(m_s - max m).
-// One workgroup per (head, 16 queries); thread = (query, D/16 columns).  Fixed order over splits.
+// One workgroup per (head, 16 queries); thread = (query, D/16 columns).  Fixed order over splits; the loads of
+// eight splits are issued together so the kernel is a few memory round trips long whatever the split count.
 template <int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_ml,
@@ -381,41 +481,56 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
                                                            int n_split, uint16_t* __restrict__ out, int64_t osh, int64_t osn,
                                                            float* __restrict__ lse) {
   constexpr int kPerThread = D / 16;
+  constexpr int kVec = kPerThread / 4;
+  constexpr int kBatch = 8;
   const int h = blockIdx.y;
   const int a = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int mc = (threadIdx.x & 15) * kPerThread;
-  const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  if (a >= n_act) return;
+  if (a >= max_active) return;
   const int64_t row0 = ((int64_t)h * q_pad + a) * n_split;
   const float2* ml = reinterpret_cast<const float2*>(part_ml) + row0;
-  float mmax = -INFINITY;
-  for (int s = 0; s < n_split; ++s) mmax = fmaxf(mmax, ml[s].x);
+  const float* po = part_o + row0 * D + mc;
   float acc_o[kPerThread];
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) acc_o[i] = 0.f;
-  float lsum = 0.f;
-  for (int s = 0; s < n_split; ++s) {
-    const float2 v = ml[s];
-    if (!(v.y > 0.f)) continue;
-    const float f = __builtin_amdgcn_exp2f(v.x - mmax);
-    lsum += f * v.y;
-    const float* src = part_o + (row0 + s) * D + mc;
+  float mrun = -INFINITY, lsum = 0.f;
+  for (int s0 = 0; s0 < n_split; s0 += kBatch) {
+    float2 v[kBatch];
+    float4 x[kBatch][kVec];
 #pragma unroll
-    for (int i = 0; i < kPerThread; i += 4) {
-      const float4 x = *reinterpret_cast<const float4*>(src + i);
-      acc_o[i] += f * x.x;
-      acc_o[i + 1] += f * x.y;
-      acc_o[i + 2] += f * x.z;
-      acc_o[i + 3] += f * x.w;
+    for (int u = 0; u < kBatch; ++u) {
+      const int s = min(s0 + u, n_split - 1);  // clamped: stays in bounds, ignored below
+      v[u] = ml[s];
+#pragma unroll
+      for (int i = 0; i < kVec; ++i) x[u][i] = *reinterpret_cast<const float4*>(po + (int64_t)s * D + 4 * i);
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (s0 + u < n_split && v[u].y > 0.f) {
+        const float m_new = fmaxf(mrun, v[u].x);
+        const float f_old = __builtin_amdgcn_exp2f(mrun - m_new);
+        const float f = __builtin_amdgcn_exp2f(v[u].x - m_new);
+        lsum = lsum * f_old + f * v[u].y;
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+          acc_o[4 * i] = acc_o[4 * i] * f_old + f * x[u][i].x;
+          acc_o[4 * i + 1] = acc_o[4 * i + 1] * f_old + f * x[u][i].y;
+          acc_o[4 * i + 2] = acc_o[4 * i + 2] * f_old + f * x[u][i].z;
+          acc_o[4 * i + 3] = acc_o[4 * i + 3] * f_old + f * x[u][i].w;
+        }
+        mrun = m_new;
+      }
     }
   }
+  const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
+  if (a >= n_act) return;
   const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
   uint16_t* dst = out + (int64_t)h * osh + (int64_t)a * osn + mc;
 #pragma unroll
   for (int i = 0; i < kPerThread; i += 2)
-    *reinterpret_cast<uint32_t*>(dst + i) = pack_bf16x2(acc_o[i] * inv, acc_o[i + 1] * inv);
+    *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
   if (lse && (threadIdx.x & 15) == 0)
-    lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mmax + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+    lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
 }
 
 template <int D, int NQT>
@@ -484,24 +599,42 @@ struct LogitArgs {
 };
 
 template <int D, int NQT>
-__global__ __launch_bounds__(256) void qk_logits_kernel(const LogitArgs p) {
+__global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
   using G = Geo<D>;
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * G::kStageBytes];
   __shared__ float ml_sh[kWavesPerGroup][NQT][16][2];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, h = blockIdx.y, qg = blockIdx.z;
-  const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
   const int q_base = qg * NQT * kQTile;
   char* stageK = lds + wave * G::kStageBytes;
   const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
 
+  const int st_begin = split * p.per_split;
+  const int st_end = min(st_begin + p.per_split, p.n_sub);
+  int st = st_begin + wave;
+  auto tile_of = [&](int s) {
+    SubTile t;
+    t.kind = 0;
+    t.row0 = s * kSubTile;
+    t.vmask = low_mask(min(p.L - t.row0, kSubTile));
+    return t;
+  };
+  int qrow[NQT];
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) qrow[qt] = fetch_q_row(p.active_idx, q_base + qt * kQTile, p.max_active, p.n_gen, lane);
+  SubTile t = tile_of(st < st_end ? st : 0);
+  if (st < st_end) issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
+
   bf16x8 q[NQT][G::kKSteps];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt)
-    load_q_tile<D>(q[qt], Qh, p.qsn, p.active_idx, q_base + qt * kQTile, n_act, p.n_gen, lane);
+  for (int qt = 0; qt < NQT; ++qt) load_q_tile<D>(q[qt], Qh, p.qsn, qrow[qt], lane);
+  const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) mask_q_tile<D>(q[qt], q_base + qt * kQTile, n_act, lane);
 
   float m_run[NQT], l_run[NQT];
 #pragma unroll
@@ -510,40 +643,27 @@ __global__ __launch_bounds__(256) void qk_logits_kernel(const LogitArgs p) {
     l_run[qt] = 0.f;
   }
 
-  const int st_begin = split * p.per_split;
-  const int st_end = min(st_begin + p.per_split, p.n_sub);
-  for (int st = st_begin + wave; st < st_end; st += kWavesPerGroup) {
-    SubTile t;
-    t.kind = 0;
-    t.row0 = st * kSubTile;
-    const int n = min(p.L - t.row0, kSubTile);
-    t.vmask = n >= 32 ? 0xffffffffu : ((1u << n) - 1u);
-    uint4 kr[G::kLoads];
-    load_subtile<D>(kr, Kh, p.ksn, t, nullptr, lane);
-    stage_subtile<D>(stageK, kr, lane);
+  while (st < st_end) {
+    const SubTile cur = t;
+    wait_loads();
     floatx4 acc[NQT][2];
     qk_subtile<D, NQT>(acc, stageK, q, lane);
+    // the staged rows are consumed: the next sub-tile can stream in while the logits are written
+    st += kWavesPerGroup;
+    if (st < st_end) {
+      t = tile_of(st);
+      issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
+    }
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-      float s[8];
-      float mx = -INFINITY;
+      float ps[8];
+      softmax_step(acc[qt], cur.vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
+      float* dst = p.logits + ((int64_t)h * p.L + cur.row0) * p.q_pad + q_base + qt * kQTile + c;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-        const bool ok = (t.vmask >> slot) & 1u;
-        s[e] = ok ? acc[qt][e >> 2][e & 3] * p.scale_log2 : -INFINITY;
-        mx = fmaxf(mx, s[e]);
-        if (ok) p.logits[((int64_t)h * p.L + t.row0 + slot) * p.q_pad + q_base + qt * kQTile + c] = s[e];
+        if ((cur.vmask >> slot) & 1u) dst[(int64_t)slot * p.q_pad] = acc[qt][e >> 2][e & 3] * p.scale_log2;
       }
-      mx = group_max(mx);
-      const float m_new = fmaxf(m_run[qt], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      float lsum = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) lsum += __builtin_amdgcn_exp2f(s[e] - m_use);
-      lsum = group_sum(lsum);
-      l_run[qt] = l_run[qt] * __builtin_amdgcn_exp2f(m_run[qt] - m_use) + lsum;
-      m_run[qt] = m_new;
     }
   }
 

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kTopkThreads) void select_queries_kernel(
     int32_t* __restrict__ focus_idx, int32_t* __restrict__ active_idx, int max_active, int32_t* __restrict__ counts) {
   __shared__ TopkShared sm;
   __shared__ uint8_t flags[kSelectMaxGen];
-  auto keyfn = [&](int i, uint32_t& key) -> bool {
+  auto keyfn = [=](int i, uint32_t& key) -> bool {
     key = order_key(conf[i]);
     return masked == nullptr || masked[i] != 0;
   };
@@ -35,12 +35,18 @@ __global__ __launch_bounds__(kTopkThreads) void select_queries_kernel(
       if (flags[i]) return true;
     return false;
   };
-  uint32_t cnt = 0;
-  for (int j = c0; j < c1; ++j) cnt += is_active(lo + j);
   uint32_t total;
-  uint32_t pos = block_exclusive_scan(cnt, sm.wsum, &total);
-  for (int j = c0; j < c1; ++j)
-    if (is_active(lo + j)) active_idx[pos++] = lo + j;
+  if (n <= nt) {
+    const bool act = tid < n && is_active(lo + tid);
+    const uint32_t pos = block_flag_scan(act, sm.wsum, &total);
+    if (act) active_idx[pos] = lo + tid;
+  } else {
+    uint32_t cnt = 0;
+    for (int j = c0; j < c1; ++j) cnt += is_active(lo + j);
+    uint32_t pos = block_exclusive_scan(cnt, sm.wsum, &total);
+    for (int j = c0; j < c1; ++j)
+      if (is_active(lo + j)) active_idx[pos++] = lo + j;
+  }
   for (int i = (int)total + tid; i < max_active; i += nt) active_idx[i] = -1;
   if (tid == 0) counts[1] = (int32_t)total;
 }
@@ -55,21 +61,70 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
 }
 
 // =====================================================================================================
-// Generic top-k over a float array (Top-C over R_b, Top-N_sink over S_j).  One workgroup.
+// Top-k over a float array that may first have to be assembled from per-head partial sums:
+//   values[j] = scale * sum_{h < n_parts} part[h * n + j]   (fixed order over h), written to values_out,
+// then Top-k over values[0..n).  With part == nullptr the values are read as they are.  One workgroup.
+// Used for Top-C over R_b (n_parts = H partial relevances) and Top-N_sink over S_j (n_parts = 0).
 // =====================================================================================================
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ values, int n, int k,
-                                                            int32_t* __restrict__ out) {
+__global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* __restrict__ part, int n_parts,
+                                                                   const int32_t* __restrict__ counts, int n_focus_max,
+                                                                   float* __restrict__ values, int n, int k,
+                                                                   int32_t* __restrict__ out) {
   __shared__ TopkShared sm;
-  auto keyfn = [&](int i, uint32_t& key) -> bool {
-    key = order_key(values[i]);
-    return true;
-  };
-  block_topk(keyfn, n, k, out, nullptr, nullptr, sm);
+  const int tid = threadIdx.x, nt = blockDim.x;
+  float mine = 0.f;
+  if (part != nullptr) {
+    const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
+    const float scale = n_f > 0 ? 1.f / ((float)n_f * (float)n_parts) : 0.f;
+    for (int j = tid; j < n; j += nt) {
+      float acc = 0.f;
+      int h = 0;
+      for (; h + 32 <= n_parts; h += 32) {  // 32 independent loads: one memory round trip for 32 heads
+        float v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = part[(int64_t)(h + u) * n + j];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) acc += v[u];
+      }
+      for (; h + 8 <= n_parts; h += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(h + u) * n + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+      }
+      for (; h < n_parts; ++h) acc += part[(int64_t)h * n + j];
+      acc *= scale;
+      values[j] = acc;
+      mine = acc;  // the value of element tid when n <= nt
+    }
+    if (n > nt) {  // the radix path re-reads values written by other threads of the workgroup
+      __threadfence_block();
+      __syncthreads();
+    }
+  } else if (tid < n) {
+    mine = values[tid];
+  }
+  if (k <= 0) return;
+  if (n <= nt) {
+    auto keyfn = [=](int, uint32_t& key) -> bool {  // only ever asked for i == tid on this path
+      key = order_key(mine);
+      return true;
+    };
+    block_topk(keyfn, n, k, out, nullptr, nullptr, sm);
+  } else {
+    auto keyfn = [=](int i, uint32_t& key) -> bool {
+      key = order_key(values[i]);
+      return true;
+    };
+    block_topk(keyfn, n, k, out, nullptr, nullptr, sm);
+  }
 }
 
-hipError_t launch_topk(const float* values, int n, int k, int32_t* out, hipStream_t st) {
+hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* counts, int n_focus_max, float* values, int n,
+                              int k, int32_t* out, hipStream_t st) {
   const int threads = n <= 64 ? 64 : (n <= 256 ? 256 : kTopkThreads);
-  hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(threads), 0, st, values, n, k, out);
+  hipLaunchKernelGGL(reduce_topk_kernel, dim3(1), dim3(threads), 0, st, part, n_parts, counts, n_focus_max, values, n, k, out);
   return hipGetLastError();
 }
 
@@ -126,55 +181,79 @@ hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, 
 }
 
 // =====================================================================================================
-// Block relevance (Eq. 7): R_b = (1/H) sum_h qbar^h . kbar^h_b with qbar^h the mean of the focus queries.
-// One workgroup per block; each thread owns fixed 8-wide slices of the (head, d) axis, rebuilds its slice
-// of qbar from the few focus rows of Q (L2 hits) and multiplies it with its slice of kbar; the workgroup
-// sum runs in a fixed order, so R_b does not depend on scheduling.
+// Block relevance (Eq. 7), per-head partial sums: part[h, b] = qsum^h . kbar^h_b with qsum^h the SUM of the
+// focus queries of head h; the 1/(|I_focus| H) factor and the sum over heads are applied, in a fixed order,
+// by reduce_topk_kernel.  One workgroup per (group of blocks, head): a thread owns one 8-wide slice of d of
+// one block row.  The kbar loads are issued first, the focus indices are fetched speculatively (all
+// n_focus_max slots, masked by the device-side count afterwards) and the Q rows are loaded eight at a time,
+// so the whole kernel is three dependent memory round trips long.
 // =====================================================================================================
 template <int D>
-__global__ __launch_bounds__(256) void block_relevance_kernel(const uint16_t* __restrict__ Q, int64_t qsh, int64_t qsn,
-                                                              const int32_t* __restrict__ focus_idx,
-                                                              const int32_t* __restrict__ counts, int n_focus_max,
-                                                              int n_gen, const float* __restrict__ kbar, int H, int n_b,
-                                                              float* __restrict__ R) {
-  constexpr int CPR = D / 8;
-  __shared__ float wsum[4];
-  const int b = blockIdx.x;
-  const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
-  float acc = 0.f;
-  for (int e = threadIdx.x; e < H * CPR; e += 256) {
-    const int h = e / CPR, c = e % CPR;
-    float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const uint16_t* qb = Q + (int64_t)h * qsh + c * 8;
-    for (int f = 0; f < n_f; ++f) {
-      const int row = focus_idx[f];
-      if (row < 0 || row >= n_gen) continue;
-      add_bf16x8(qs, *reinterpret_cast<const uint4*>(qb + (int64_t)row * qsn));
+__global__ __launch_bounds__(256) void relevance_partial_kernel(const uint16_t* __restrict__ Q, int64_t qsh, int64_t qsn,
+                                                                const int32_t* __restrict__ focus_idx,
+                                                                const int32_t* __restrict__ counts, int n_focus_max,
+                                                                int n_gen, const float* __restrict__ kbar, int n_b,
+                                                                float* __restrict__ part) {
+  constexpr int CPR = D / 8;      // lanes per block row
+  constexpr int RPP = 256 / CPR;  // block rows per pass
+  constexpr int PASSES = 2;
+  __shared__ int rows_sh[256];
+  const int t = threadIdx.x, c = t % CPR, r = t / CPR;
+  const int h = blockIdx.y, b0 = blockIdx.x * (RPP * PASSES);
+  float4 k0[PASSES], k1[PASSES];
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) {
+    const int b = b0 + p * RPP + r;
+    if (b < n_b) {
+      const float4* kp = reinterpret_cast<const float4*>(kbar + ((int64_t)h * n_b + b) * D + c * 8);
+      k0[p] = kp[0];
+      k1[p] = kp[1];
+    } else {
+      k0[p] = k1[p] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    const float4* kp = reinterpret_cast<const float4*>(kbar + ((int64_t)h * n_b + b) * D + c * 8);
-    const float4 k0 = kp[0], k1 = kp[1];
-    acc += qs[0] * k0.x + qs[1] * k0.y + qs[2] * k0.z + qs[3] * k0.w + qs[4] * k1.x + qs[5] * k1.y + qs[6] * k1.z +
-           qs[7] * k1.w;
   }
-  acc = wave_sum(acc);
-  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const float tot = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-    R[b] = n_f > 0 ? tot / ((float)n_f * (float)H) : 0.f;
+  int my_row = t < n_focus_max ? focus_idx[t] : -1;  // speculative: valid only below the device-side count
+  const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
+  float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const uint16_t* qb = Q + (int64_t)h * qsh + c * 8;
+  for (int f0 = 0; f0 < n_f; f0 += 256) {
+    if (f0 > 0) my_row = f0 + t < n_focus_max ? focus_idx[f0 + t] : -1;
+    __syncthreads();
+    rows_sh[t] = (f0 + t < n_f && my_row >= 0 && my_row < n_gen) ? my_row : -1;
+    __syncthreads();
+    const int cnt = min(256, n_f - f0);
+    for (int f = 0; f < cnt; f += 8) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int row = f + u < cnt ? rows_sh[f + u] : -1;
+        v[u] = row >= 0 ? *reinterpret_cast<const uint4*>(qb + (int64_t)row * qsn) : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) add_bf16x8(qs, v[u]);
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) {
+    float dot = qs[0] * k0[p].x + qs[1] * k0[p].y + qs[2] * k0[p].z + qs[3] * k0[p].w + qs[4] * k1[p].x +
+                qs[5] * k1[p].y + qs[6] * k1[p].z + qs[7] * k1[p].w;
+#pragma unroll
+    for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+    const int b = b0 + p * RPP + r;
+    if (c == 0 && b < n_b) part[(int64_t)h * n_b + b] = dot;
   }
 }
 
 hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const int32_t* counts, int n_focus_max,
-                                  const float* kbar, const focus_shape& s, float* scores, hipStream_t st) {
+                                  const float* kbar, const focus_shape& s, float* part, hipStream_t st) {
   const int n_b = ceil_div(s.n_ctx, s.block);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (s.head_dim == 128)
-    hipLaunchKernelGGL(block_relevance_kernel<128>, dim3(n_b), dim3(256), 0, st, q, s.q_stride_h, s.q_stride_n, focus_idx,
-                       counts, n_focus_max, s.n_gen, kbar, s.n_heads, n_b, scores);
+    hipLaunchKernelGGL(relevance_partial_kernel<128>, dim3(ceil_div(n_b, 32), s.n_heads), dim3(256), 0, st, q, s.q_stride_h,
+                       s.q_stride_n, focus_idx, counts, n_focus_max, s.n_gen, kbar, n_b, part);
   else
-    hipLaunchKernelGGL(block_relevance_kernel<64>, dim3(n_b), dim3(256), 0, st, q, s.q_stride_h, s.q_stride_n, focus_idx,
-                       counts, n_focus_max, s.n_gen, kbar, s.n_heads, n_b, scores);
+    hipLaunchKernelGGL(relevance_partial_kernel<64>, dim3(ceil_div(n_b, 64), s.n_heads), dim3(256), 0, st, q, s.q_stride_h,
+                       s.q_stride_n, focus_idx, counts, n_focus_max, s.n_gen, kbar, n_b, part);
   return hipGetLastError();
 }
 
@@ -185,26 +264,36 @@ hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const
 // =====================================================================================================
 __global__ __launch_bounds__(256) void lse_combine_kernel(const float* __restrict__ part_ml, int rows, int n_split,
                                                           float* __restrict__ lse2) {
-  const int r = blockIdx.x * 256 + threadIdx.x;  // r = h * q_pad + q
+  // one wavefront per row r = h * q_pad + q; lanes stride over the splits, so the loads are independent
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (r >= rows) return;
   const float2* p = reinterpret_cast<const float2*>(part_ml) + (int64_t)r * n_split;
-  float m = -INFINITY;
-  for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s].x);
-  float l = 0.f;
-  for (int s = 0; s < n_split; ++s) {
+  float m = -INFINITY, l = 0.f;
+  for (int s = lane; s < n_split; s += kWave) {
     const float2 v = p[s];
-    if (v.y > 0.f) l += v.y * __builtin_amdgcn_exp2f(v.x - m);
+    if (v.y > 0.f) {
+      const float m_new = fmaxf(m, v.x);
+      l = l * __builtin_amdgcn_exp2f(m - m_new) + v.y * __builtin_amdgcn_exp2f(v.x - m_new);
+      m = m_new;
+    }
   }
-  lse2[r] = l > 0.f ? m + __builtin_amdgcn_logf(l) : INFINITY;  // v_log_f32 is log2; INF makes exp2(x - lse) zero
+  float mmax = m;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, o, kWave));
+  float ls = l > 0.f ? l * __builtin_amdgcn_exp2f(m - mmax) : 0.f;
+  ls = wave_sum(ls);
+  if (lane == 0) lse2[r] = ls > 0.f ? mmax + __builtin_amdgcn_logf(ls) : INFINITY;  // v_log_f32 is log2
 }
 
 hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_split, float* lse2, hipStream_t st) {
   const int rows = H * q_pad;
-  hipLaunchKernelGGL(lse_combine_kernel, dim3(ceil_div(rows, 256)), dim3(256), 0, st, part_ml, rows, n_split, lse2);
+  hipLaunchKernelGGL(lse_combine_kernel, dim3(ceil_div(rows, 4)), dim3(256), 0, st, part_ml, rows, n_split, lse2);
   return hipGetLastError();
 }
 
 // logits: [H, L, q_pad] fp32.  Workgroup = 64 keys x 4 head groups; thread (key, hg) walks heads hg, hg+4, ...
+// QP16 = true: q_pad == 16, the loads of four heads (16 x 16 bytes) are issued before the first exp2.
+template <bool QP16>
 __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restrict__ logits, const float* __restrict__ lse2,
                                                           const int32_t* __restrict__ counts, int max_active, int H, int L,
                                                           int q_pad, float* __restrict__ col_mass) {
@@ -214,19 +303,50 @@ __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restric
   const int j = blockIdx.x * 64 + kj;
   float acc = 0.f;
   if (j < L) {
-    for (int h = hg; h < H; h += 4) {
-      const float* lp = logits + ((int64_t)h * L + j) * q_pad;
-      const float* ls = lse2 + (int64_t)h * q_pad;
-      float a = 0.f;
-      for (int i0 = 0; i0 < n_act; i0 += 4) {
-        const float4 x = *reinterpret_cast<const float4*>(lp + i0);
-        const float4 z = *reinterpret_cast<const float4*>(ls + i0);
-        a += __builtin_amdgcn_exp2f(x.x - z.x);
-        if (i0 + 1 < n_act) a += __builtin_amdgcn_exp2f(x.y - z.y);
-        if (i0 + 2 < n_act) a += __builtin_amdgcn_exp2f(x.z - z.z);
-        if (i0 + 3 < n_act) a += __builtin_amdgcn_exp2f(x.w - z.w);
+    if (QP16) {
+      for (int h0 = hg; h0 < H; h0 += 16) {
+        float4 x[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int h = h0 + 4 * u;
+          const float4* lp = reinterpret_cast<const float4*>(logits + ((int64_t)(h < H ? h : hg) * L + j) * 16);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) x[u][i] = lp[i];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int h = h0 + 4 * u;
+          if (h < H) {
+            const float4* ls = reinterpret_cast<const float4*>(lse2 + (int64_t)h * 16);
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float4 z = ls[i];
+              const int i0 = 4 * i;
+              if (i0 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].x - z.x);
+              if (i0 + 1 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].y - z.y);
+              if (i0 + 2 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].z - z.z);
+              if (i0 + 3 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].w - z.w);
+            }
+            acc += a;
+          }
+        }
       }
-      acc += a;
+    } else {
+      for (int h = hg; h < H; h += 4) {
+        const float* lp = logits + ((int64_t)h * L + j) * q_pad;
+        const float* ls = lse2 + (int64_t)h * q_pad;
+        float a = 0.f;
+        for (int i0 = 0; i0 < n_act; i0 += 4) {
+          const float4 x = *reinterpret_cast<const float4*>(lp + i0);
+          const float4 z = *reinterpret_cast<const float4*>(ls + i0);
+          a += __builtin_amdgcn_exp2f(x.x - z.x);
+          if (i0 + 1 < n_act) a += __builtin_amdgcn_exp2f(x.y - z.y);
+          if (i0 + 2 < n_act) a += __builtin_amdgcn_exp2f(x.z - z.z);
+          if (i0 + 3 < n_act) a += __builtin_amdgcn_exp2f(x.w - z.w);
+        }
+        acc += a;
+      }
     }
   }
   red[hg][kj] = acc;
@@ -239,8 +359,12 @@ __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restric
 
 hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active, int H,
                               int L, int q_pad, float* col_mass, hipStream_t st) {
-  hipLaunchKernelGGL(column_mass_kernel, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active, H, L,
-                     q_pad, col_mass);
+  if (q_pad == 16)
+    hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active, H,
+                       L, q_pad, col_mass);
+  else
+    hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active,
+                       H, L, q_pad, col_mass);
   return hipGetLastError();
 }
 
