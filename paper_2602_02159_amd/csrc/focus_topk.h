@@ -6,7 +6,8 @@
 //
 // Two paths, one workgroup each:
 //   * n <= blockDim : rank by counting — every thread counts how many candidates beat its own, reading the
-//                     staged keys four at a time from LDS (broadcast reads, no dependent chain).
+//                     staged keys four at a time from LDS (broadcast reads, no dependent chain); the tie rule
+//                     costs extra compares only against the keys of the thread's own wavefront.
 //   * larger n      : every thread keeps a contiguous run of up to 32 keys in registers (one pass over
 //                     memory); a 4-pass radix select over the 32-bit order-preserving key finds the k-th
 //                     key T and how many keys equal to T are still needed; an ordered compaction then emits
@@ -69,28 +70,37 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
     __syncthreads();
     sm.keys[tid] = mine;  // threads past n store 0: never beats anything
     __syncthreads();
-    // rank = #{j : key_j > mine} + #{j < tid : key_j == mine}.  The first count costs one compare and one
-    // add-with-carry per key; the tie term is only evaluated when some key of the workgroup is not unique.
+    // rank = #{j < tid : key_j >= mine} + #{j > tid : key_j > mine}.  Keys are read four at a time; groups that lie
+    // entirely below (above) the index range of this wavefront need one compare and one add per key, only the 16
+    // groups that overlap the wavefront's own indices need the index test.
     const uint4* k4 = reinterpret_cast<const uint4*>(sm.keys);
     const int groups = (n + 3) >> 2;
-    uint32_t gt = 0, ge = 0;
-#pragma unroll 8
-    for (int j4 = 0; j4 < groups; ++j4) {
+    const int g_lo = min(__builtin_amdgcn_readfirstlane(tid >> 6) * 16, groups), g_hi = min(g_lo + 16, groups);
+    uint32_t rank = 0;
+#pragma unroll 4
+    for (int j4 = 0; j4 < g_lo; ++j4) {
       const uint4 v = k4[j4];
-      gt += (v.x > mine) + (v.y > mine) + (v.z > mine) + (v.w > mine);
-      ge += (v.x >= mine) + (v.y >= mine) + (v.z >= mine) + (v.w >= mine);
+      rank += (v.x >= mine);
+      rank += (v.y >= mine);
+      rank += (v.z >= mine);
+      rank += (v.w >= mine);
     }
-    uint32_t rank = gt;
-    if (__syncthreads_or(myvalid && ge - gt > 1u)) {
-      uint32_t eq_before = 0;
-#pragma unroll 8
-      for (int j4 = 0; j4 < groups; ++j4) {
-        const uint4 v = k4[j4];
-        const int j = j4 << 2;
-        eq_before += (v.x == mine && j < tid) + (v.y == mine && j + 1 < tid) + (v.z == mine && j + 2 < tid) +
-                     (v.w == mine && j + 3 < tid);
-      }
-      rank += eq_before;
+#pragma unroll 4
+    for (int j4 = g_lo; j4 < g_hi; ++j4) {
+      const uint4 v = k4[j4];
+      const int j = j4 << 2;
+      rank += (v.x > mine) || (v.x == mine && j < tid);
+      rank += (v.y > mine) || (v.y == mine && j + 1 < tid);
+      rank += (v.z > mine) || (v.z == mine && j + 2 < tid);
+      rank += (v.w > mine) || (v.w == mine && j + 3 < tid);
+    }
+#pragma unroll 4
+    for (int j4 = g_hi; j4 < groups; ++j4) {
+      const uint4 v = k4[j4];
+      rank += (v.x > mine);
+      rank += (v.y > mine);
+      rank += (v.z > mine);
+      rank += (v.w > mine);
     }
     const bool sel = myvalid && rank < (uint32_t)k;
     const uint32_t pos = block_flag_scan(sel, sm.wsum, &total);
