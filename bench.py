@@ -73,6 +73,21 @@ def parse_pmc(fetch_db: str, write_db: str, workload: str) -> int:
     return 0
 
 
+def parse_trace(db: str) -> int:
+    """Per-kernel duration table from a `rocprofv3 --kernel-trace --stats` result database of a bench.py run.
+    Launches are grouped by (kernel, grid) because the dense comparison runs through the same kernel as the sparse path."""
+    import sqlite3
+    c = sqlite3.connect(db)
+    rows = c.execute("select name, grid_x, grid_y, grid_z, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
+                     "from kernels where name like '%focus::%' group by name, grid_x, grid_y, grid_z order by sum(end-start) desc").fetchall()
+    print(f"| kernel | grid (threads) | launches | avg us | min us | max us | total ms |")
+    print("|---|---|---|---|---|---|---|")
+    for n, gx, gy, gz, cnt, avg, mn, mx, sm in rows:
+        short = n.replace("void focus::", "").replace("focus::", "").split("(")[0]
+        print(f"| `{short}` | {gx}x{gy}x{gz} | {cnt} | {avg / 1e3:.2f} | {mn / 1e3:.2f} | {mx / 1e3:.2f} | {sm / 1e6:.3f} |")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,7 +104,10 @@ def main() -> int:
                          "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
     ap.add_argument("--parse-pmc", nargs=2, metavar=("FETCH_DB", "WRITE_DB"),
                     help="turn the two rocprofv3 --pmc result databases of a `--mode pmc` run into profiles/hbm_traffic_<workload>.json")
+    ap.add_argument("--parse-trace", metavar="DB", help="print the per-kernel table of a rocprofv3 --kernel-trace database")
     args = ap.parse_args()
+    if args.parse_trace:
+        return parse_trace(args.parse_trace)
     if args.parse_pmc:
         return parse_pmc(args.parse_pmc[0], args.parse_pmc[1], args.workload)
     if args.gpus != 1:
