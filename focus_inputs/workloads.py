@@ -87,7 +87,15 @@ CTX32K = _mk_single("ctx32k", 3, 32768, 0.03)
 STACK32K = CTX32K.with_(name="stack32k", n_layers=32, seed=_BASE_SEED + 4, probe_layer=16, first_sparse_layer=17,
                         sink_positions=(0, 1, 8191, 20000))
 
-WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K)}
+# The paper's own hyper-parameters (Sec. "Implementation details": rho = 4, w = 8, alpha = 0.5, N_sink = 0.01 M,
+# prompt block 64) on the 32K shape, one token unmasked per step (generation length = steps): k = round(4 * 1) = 4,
+# 9-wide windows, 256 of 512 blocks kept, 327 sinks.  Not a timed configuration; used to check the same kernels
+# on the shapes the paper ran.
+PAPER32K = Workload(name="paper32k", n_layers=1, n_heads=32, head_dim=128, n_ctx=32768, n_resp=64, n_gen=64, block=64,
+                    k_focus=4, window=8, n_keep=256, n_sink=327, sink_positions=_seeded_sinks(_BASE_SEED + 5, 32768, 4),
+                    conf_model="correlated", seed=_BASE_SEED + 5)
+
+WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K, PAPER32K)}
 
 
 def strong_sinks(w: Workload, logit_shift: float = 6.0) -> Workload:

@@ -11,6 +11,7 @@
  *     focus_block_means      whenever the prompt K of a layer is refreshed -> K_bar (cacheable)
  *     focus_block_scores     per sparse layer                   -> R_b, B_relevant
  *     focus_sparse_attn      per sparse layer                   -> Attn
+ *     focus_sparse_layer     = focus_block_scores + focus_sparse_attn of one layer, fused into fewer launches
  *
  * Conventions shared by every entry point
  *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
@@ -65,7 +66,8 @@ typedef struct focus_shape {
 typedef enum focus_fn {
   FOCUS_FN_BLOCK_SCORES = 1,
   FOCUS_FN_FIND_SINKS = 2,
-  FOCUS_FN_SPARSE_ATTN = 3
+  FOCUS_FN_SPARSE_ATTN = 3,
+  FOCUS_FN_SPARSE_LAYER = 4
 } focus_fn;
 
 /*
@@ -141,6 +143,20 @@ int focus_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* c
                       const void* K, const void* V, const focus_shape* shape, const int32_t* kept_blocks,
                       int32_t n_keep, const int32_t* sink_idx, int32_t n_sink, void* out, float* lse,
                       void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * One sparse layer of Alg. 1 in a single call: block relevance (Eq. 7), Top-C, index union (Eq. 8) and sparse
+ * attention (Eq. 9) — exactly focus_block_scores followed by focus_sparse_attn, with the same arguments and
+ * bit-identical outputs (scores, kept_blocks, out, lse), but in three kernel launches instead of four: the
+ * attention kernel ranks the blocks itself from the per-head partial relevances instead of waiting for a
+ * separate Top-C kernel.  kbar NULL: the block means are built from K first (one more launch).
+ * With more than 256 prompt blocks the call falls back to the separate kernels.
+ */
+int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* active_idx, const int32_t* counts,
+                       int32_t n_focus_max, int32_t max_active, const void* K, const void* V, const float* kbar,
+                       const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink,
+                       float* scores, int32_t* kept_blocks, void* out, float* lse, void* workspace, size_t ws_bytes,
+                       void* stream);
 
 /* Bytes of workspace `fn` needs for this shape; 0 on invalid arguments.  [host] only. */
 size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep,

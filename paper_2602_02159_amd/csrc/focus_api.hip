@@ -129,6 +129,20 @@ static AttnWs ws_attn(const focus_shape& s, const SplitPlan& p) {
   return w;
 }
 
+struct LayerWs {
+  size_t attn, total;
+  ScoreWs sc;
+  AttnWs at;
+};
+static LayerWs ws_layer(const focus_shape& s, const SplitPlan& p) {
+  LayerWs w;
+  w.sc = ws_block_scores(s);
+  w.at = ws_attn(s, p);
+  w.attn = w.sc.total;
+  w.total = w.attn + w.at.total;
+  return w;
+}
+
 }  // namespace focus
 
 using namespace focus;
@@ -156,6 +170,11 @@ size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_a
           n_sink > shape->n_ctx)
         return 0;
       return ws_attn(*shape, plan_attention(*shape, max_active, n_keep, n_sink)).total;
+    case FOCUS_FN_SPARSE_LAYER:
+      if (max_active < 1 || max_active > shape->n_gen || n_keep < 0 || n_keep > n_b || n_sink < 0 ||
+          n_sink > shape->n_ctx)
+        return 0;
+      return ws_layer(*shape, plan_attention(*shape, max_active, n_keep, n_sink)).total;
     default:
       fail(FOCUS_EINVAL, "focus_workspace_bytes: unknown function id %d", fn);
       return 0;
@@ -274,9 +293,62 @@ int focus_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* c
   char* ws = static_cast<char*>(workspace);
   hipError_t e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, kept_blocks, n_keep, sink_idx, n_sink, p,
                                     out, lse, ws ? reinterpret_cast<float*>(ws + w.part_o) : nullptr,
-                                    ws ? reinterpret_cast<float*>(ws + w.part_ml) : nullptr,
+                                    ws ? reinterpret_cast<float*>(ws + w.part_ml) : nullptr, nullptr,
                                     static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return launch_fail("focus_sparse_attn", e);
+  return FOCUS_OK;
+}
+
+int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* active_idx, const int32_t* counts,
+                       int32_t n_focus_max, int32_t max_active, const void* K, const void* V, const float* kbar,
+                       const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink, float* scores,
+                       int32_t* kept_blocks, void* out, float* lse, void* workspace, size_t ws_bytes, void* stream) {
+  if (int rc = check_shape(shape, true, true, true, true)) return rc;
+  if (!Q || !focus_idx || !active_idx || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_sparse_layer: NULL pointer");
+  const int n_b = ceil_div(shape->n_ctx, shape->block);
+  if (n_focus_max < 1 || n_focus_max > shape->n_gen) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_focus_max=%d not in [1, n_gen]", n_focus_max);
+  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "focus_sparse_layer: max_active=%d not in [1, n_gen]", max_active);
+  if (n_keep < 0 || n_keep > n_b) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_keep=%d not in [0, n_b=%d]", n_keep, n_b);
+  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_sink=%d not in [0, n_ctx]", n_sink);
+  if ((n_keep > 0 && !kept_blocks) || (n_sink > 0 && !sink_idx)) return fail(FOCUS_EINVAL, "focus_sparse_layer: index array is NULL");
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || (kbar && !aligned16(kbar)))
+    return fail(FOCUS_EINVAL, "focus_sparse_layer: pointers must be 16-byte aligned");
+  const SplitPlan p = plan_attention(*shape, max_active, n_keep, n_sink);
+  const LayerWs w = ws_layer(*shape, p);
+  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "focus_sparse_layer: workspace needs %zu bytes, 16-byte aligned", w.total);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* ws_kbar = reinterpret_cast<float*>(ws + w.sc.kbar);
+  float* part = reinterpret_cast<float*>(ws + w.sc.part);
+  float* R = scores ? scores : reinterpret_cast<float*>(ws + w.sc.scores);
+  float* part_o = reinterpret_cast<float*>(ws + w.attn + w.at.part_o);
+  float* part_ml = reinterpret_cast<float*>(ws + w.attn + w.at.part_ml);
+  hipError_t e;
+  if (!kbar) {
+    e = launch_block_means(K, *shape, ws_kbar, st);
+    if (e != hipSuccess) return launch_fail("focus_sparse_layer(block means)", e);
+    kbar = ws_kbar;
+  }
+  const bool fused = n_b <= kFusedMaxBlocks && n_keep > 0;
+  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(relevance)", e);
+  if (fused) {
+    FusedTopC f;
+    f.rel_part = part;
+    f.scores_out = R;
+    f.kept_out = kept_blocks;
+    f.n_focus_max = n_focus_max;
+    e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, nullptr, n_keep, sink_idx, n_sink, p, out, lse,
+                           part_o, part_ml, &f, st);
+    if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
+    return FOCUS_OK;
+  }
+  e = launch_reduce_topk(part, shape->n_heads, counts, n_focus_max, R, n_b, n_keep, kept_blocks, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(top-C)", e);
+  e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, kept_blocks, n_keep, sink_idx, n_sink, p, out, lse,
+                         part_o, part_ml, nullptr, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
   return FOCUS_OK;
 }
 

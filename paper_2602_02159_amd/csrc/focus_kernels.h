@@ -48,9 +48,18 @@ hipError_t launch_column_mass(const float* logits, const float* lse2, const int3
 hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                             const void* K, const focus_shape& s, const SplitPlan& p, float* logits, float* part_ml,
                             hipStream_t st);
+// Extra arguments of the fused layer path: the attention kernel ranks the blocks itself from the per-head partial
+// relevances (n_b <= kFusedMaxBlocks).
+constexpr int kFusedMaxBlocks = 256;
+struct FusedTopC {
+  const float* rel_part;  // [H, n_b] from launch_block_relevance
+  float* scores_out;      // [n_b] or null
+  int32_t* kept_out;      // [n_keep]
+  int n_focus_max;
+};
 hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                               const void* K, const void* V, const focus_shape& s, const int32_t* kept_blocks,
                               int n_keep, const int32_t* sink_idx, int n_sink, const SplitPlan& p, void* out,
-                              float* lse, float* part_o, float* part_ml, hipStream_t st);
+                              float* lse, float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st);
 
 }  // namespace focus

@@ -21,8 +21,11 @@
 // exponentiated values already sit in B-operand layout for the second product O^T[dcol][query] = V^T . P^T,
 // where the contraction slot (g, e) stands for key 16*(e/4) + 4g + (e%4) of the sub-tile on both operands.
 // The V^T operand is read from the row-major staged tile with the transposing LDS read ds_read_b64_tr_b16.
+#include <cstdlib>
+
 #include "focus_common.h"
 #include "focus_kernels.h"
+#include "focus_topk.h"
 
 namespace focus {
 
@@ -305,11 +308,75 @@ struct AttnArgs {
   int H, M, N, B, n_b, n_gen, n_keep, n_sink, max_active;
   int sub_per_block, n_sub, per_split, n_split, q_pad;
   float scale_log2;
+  // fused layer path only: per-head partial relevances in, scores / kept blocks out
+  const float* rel_part;  // [H, n_b]
+  float* scores_out;      // [n_b] or null
+  int32_t* kept_out;      // [n_keep]
+  int n_focus_max;
 };
 
-template <int D, int NQT>
+// Merge of per-split partial results for one (head, active row a): out = sum_s f_s O_s / sum_s f_s l_s with
+// f_s = exp2(m_s - running max), splits taken in index order, eight loads in flight at a time.  Thread = D/16 columns.
+template <int D>
+__device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, const float* __restrict__ part_ml, int h, int a,
+                                             int mc, int q_pad, int n_split, int max_active, uint16_t* __restrict__ out,
+                                             int64_t osh, int64_t osn, float* __restrict__ lse, bool write_lse) {
+  constexpr int kPerThread = D / 16;
+  constexpr int kVec = kPerThread / 4;
+  constexpr int kBatch = 8;
+  const int64_t row0 = ((int64_t)h * q_pad + a) * n_split;
+  const float2* ml = reinterpret_cast<const float2*>(part_ml) + row0;
+  const float* po = part_o + row0 * D + mc;
+  float acc_o[kPerThread];
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) acc_o[i] = 0.f;
+  float mrun = -INFINITY, lsum = 0.f;
+  for (int s0 = 0; s0 < n_split; s0 += kBatch) {
+    float2 v[kBatch];
+    float4 x[kBatch][kVec];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int s = min(s0 + u, n_split - 1);  // clamped: stays in bounds, ignored below
+      v[u] = ml[s];
+#pragma unroll
+      for (int i = 0; i < kVec; ++i) x[u][i] = *reinterpret_cast<const float4*>(po + (int64_t)s * D + 4 * i);
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (s0 + u < n_split && v[u].y > 0.f) {
+        const float m_new = fmaxf(mrun, v[u].x);
+        const float f_old = __builtin_amdgcn_exp2f(mrun - m_new);
+        const float f = __builtin_amdgcn_exp2f(v[u].x - m_new);
+        lsum = lsum * f_old + f * v[u].y;
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+          acc_o[4 * i] = acc_o[4 * i] * f_old + f * x[u][i].x;
+          acc_o[4 * i + 1] = acc_o[4 * i + 1] * f_old + f * x[u][i].y;
+          acc_o[4 * i + 2] = acc_o[4 * i + 2] * f_old + f * x[u][i].z;
+          acc_o[4 * i + 3] = acc_o[4 * i + 3] * f_old + f * x[u][i].w;
+        }
+        mrun = m_new;
+      }
+    }
+  }
+  const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+  uint16_t* dst = out + (int64_t)h * osh + (int64_t)a * osn + mc;
+#pragma unroll
+  for (int i = 0; i < kPerThread; i += 2)
+    *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
+  if (lse && write_lse)
+    lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+}
+
+// FUSE = 0: kept_blocks comes from memory.
+// FUSE = 1 (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
+// them itself — every workgroup repeats this small computation instead of waiting for a separate Top-C kernel.
+// In both cases a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
+// behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
+template <int D, int NQT, int FUSE>
 __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
   using G = Geo<D>;
+  constexpr bool FUSED = (FUSE & 1) != 0;        // Top-C in the prologue
   constexpr int kWaveLds = 2 * G::kStageBytes;  // K stage + V stage, reused for the final merge
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * kWaveLds];
 
@@ -327,6 +394,31 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(co
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
   const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
 
+  __shared__ __attribute__((aligned(16))) char topk_raw[FUSED ? sizeof(TopkShared) : 16];
+  TopkShared& topk_sm = *reinterpret_cast<TopkShared*>(topk_raw);
+  __shared__ int32_t kept_sh[FUSED ? kFusedMaxBlocks : 1];
+  const int32_t* kept_blocks = p.kept_blocks;
+  if (FUSED) {
+    // R_b = (1 / (|I_focus| H)) sum_h part[h, b] for b = threadIdx.x (n_b <= 256), then Top-C by rank counting
+    const int tid = threadIdx.x;
+    float r = 0.f;
+    if (tid < p.n_b) r = sum_partials(p.rel_part, p.H, p.n_b, tid);
+    FOCUS_STAMP(9);
+    const int n_f = p.counts ? min(max(p.counts[0], 0), p.n_focus_max) : p.n_focus_max;
+    r *= n_f > 0 ? 1.f / ((float)n_f * (float)p.H) : 0.f;
+    auto keyfn = [=](int, uint32_t& key) -> bool {
+      key = order_key(r);
+      return true;
+    };
+    block_topk(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);
+    FOCUS_STAMP(10);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
+      if (p.scores_out && tid < p.n_b) p.scores_out[tid] = r;
+      if (tid < p.n_keep) p.kept_out[tid] = kept_sh[tid];
+    }
+    kept_blocks = kept_sh;
+  }
+
   // Order of the memory requests: the query row ids first (tiny, they return first), then the first
   // sub-tile's K and V rows as soon as its block id is known, then the query rows and the device-side count.
   const int st_begin = split * p.per_split;
@@ -340,7 +432,7 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(co
   t.row0 = 0;
   t.vmask = 0u;
   if (st < st_end) {
-    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, p.kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
     if (t.vmask != 0u) {
       issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
       issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
@@ -397,7 +489,7 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(co
     }
     st += kWavesPerGroup;
     if (st < st_end) {
-      t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, p.kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+      t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
       if (t.vmask != 0u) {
         issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
         issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
@@ -480,63 +572,21 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
                                                            const int32_t* __restrict__ counts, int max_active, int q_pad,
                                                            int n_split, uint16_t* __restrict__ out, int64_t osh, int64_t osn,
                                                            float* __restrict__ lse) {
-  constexpr int kPerThread = D / 16;
-  constexpr int kVec = kPerThread / 4;
-  constexpr int kBatch = 8;
   const int h = blockIdx.y;
   const int a = blockIdx.x * 16 + (threadIdx.x >> 4);
-  const int mc = (threadIdx.x & 15) * kPerThread;
-  if (a >= max_active) return;
-  const int64_t row0 = ((int64_t)h * q_pad + a) * n_split;
-  const float2* ml = reinterpret_cast<const float2*>(part_ml) + row0;
-  const float* po = part_o + row0 * D + mc;
-  float acc_o[kPerThread];
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i) acc_o[i] = 0.f;
-  float mrun = -INFINITY, lsum = 0.f;
-  for (int s0 = 0; s0 < n_split; s0 += kBatch) {
-    float2 v[kBatch];
-    float4 x[kBatch][kVec];
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int s = min(s0 + u, n_split - 1);  // clamped: stays in bounds, ignored below
-      v[u] = ml[s];
-#pragma unroll
-      for (int i = 0; i < kVec; ++i) x[u][i] = *reinterpret_cast<const float4*>(po + (int64_t)s * D + 4 * i);
-    }
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (s0 + u < n_split && v[u].y > 0.f) {
-        const float m_new = fmaxf(mrun, v[u].x);
-        const float f_old = __builtin_amdgcn_exp2f(mrun - m_new);
-        const float f = __builtin_amdgcn_exp2f(v[u].x - m_new);
-        lsum = lsum * f_old + f * v[u].y;
-#pragma unroll
-        for (int i = 0; i < kVec; ++i) {
-          acc_o[4 * i] = acc_o[4 * i] * f_old + f * x[u][i].x;
-          acc_o[4 * i + 1] = acc_o[4 * i + 1] * f_old + f * x[u][i].y;
-          acc_o[4 * i + 2] = acc_o[4 * i + 2] * f_old + f * x[u][i].z;
-          acc_o[4 * i + 3] = acc_o[4 * i + 3] * f_old + f * x[u][i].w;
-        }
-        mrun = m_new;
-      }
-    }
-  }
+  const int mc = (threadIdx.x & 15) * (D / 16);
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
   if (a >= n_act) return;
-  const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-  uint16_t* dst = out + (int64_t)h * osh + (int64_t)a * osn + mc;
-#pragma unroll
-  for (int i = 0; i < kPerThread; i += 2)
-    *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
-  if (lse && (threadIdx.x & 15) == 0)
-    lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+  merge_splits<D>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, out, osh, osn, lse, (threadIdx.x & 15) == 0);
 }
 
 template <int D, int NQT>
-static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, hipStream_t st) {
+static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  hipLaunchKernelGGL((sparse_attn_kernel<D, NQT>), grid, dim3(256), 0, st, a);
+  if (fused)
+    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 1>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 0>), grid, dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
@@ -547,7 +597,7 @@ static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, hipStream
 hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                               const void* K, const void* V, const focus_shape& s, const int32_t* kept_blocks, int n_keep,
                               const int32_t* sink_idx, int n_sink, const SplitPlan& p, void* out, float* lse,
-                              float* part_o, float* part_ml, hipStream_t st) {
+                              float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st) {
   AttnArgs a;
   a.Q = static_cast<const uint16_t*>(Q);
   a.K = static_cast<const uint16_t*>(K);
@@ -570,15 +620,20 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
   a.sub_per_block = ceil_div(s.block, kSubTile);
   a.n_sub = p.n_sub; a.per_split = p.per_split; a.n_split = p.n_split; a.q_pad = p.q_pad;
   a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
+  a.rel_part = fused ? fused->rel_part : nullptr;
+  a.scores_out = fused ? fused->scores_out : nullptr;
+  a.kept_out = fused ? fused->kept_out : nullptr;
+  a.n_focus_max = fused ? fused->n_focus_max : 0;
+  const bool f = fused != nullptr;
   const int nqt = p.q_tiles_per_group;
   if (s.head_dim == 128) {
-    if (nqt == 1) return launch_attn_t<128, 1>(a, p, st);
-    if (nqt == 2) return launch_attn_t<128, 2>(a, p, st);
-    return launch_attn_t<128, 4>(a, p, st);
+    if (nqt == 1) return launch_attn_t<128, 1>(a, p, f, st);
+    if (nqt == 2) return launch_attn_t<128, 2>(a, p, f, st);
+    return launch_attn_t<128, 4>(a, p, f, st);
   }
-  if (nqt == 1) return launch_attn_t<64, 1>(a, p, st);
-  if (nqt == 2) return launch_attn_t<64, 2>(a, p, st);
-  return launch_attn_t<64, 4>(a, p, st);
+  if (nqt == 1) return launch_attn_t<64, 1>(a, p, f, st);
+  if (nqt == 2) return launch_attn_t<64, 2>(a, p, f, st);
+  return launch_attn_t<64, 4>(a, p, f, st);
 }
 
 // =====================================================================================================

@@ -77,23 +77,7 @@ __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* 
     const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
     const float scale = n_f > 0 ? 1.f / ((float)n_f * (float)n_parts) : 0.f;
     for (int j = tid; j < n; j += nt) {
-      float acc = 0.f;
-      int h = 0;
-      for (; h + 32 <= n_parts; h += 32) {  // 32 independent loads: one memory round trip for 32 heads
-        float v[32];
-#pragma unroll
-        for (int u = 0; u < 32; ++u) v[u] = part[(int64_t)(h + u) * n + j];
-#pragma unroll
-        for (int u = 0; u < 32; ++u) acc += v[u];
-      }
-      for (; h + 8 <= n_parts; h += 8) {
-        float v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(h + u) * n + j];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
-      }
-      for (; h < n_parts; ++h) acc += part[(int64_t)h * n + j];
+      float acc = sum_partials(part, n_parts, n, j);
       acc *= scale;
       values[j] = acc;
       mine = acc;  // the value of element tid when n <= nt
@@ -117,7 +101,8 @@ __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* 
       key = order_key(values[i]);
       return true;
     };
-    block_topk(keyfn, n, k, out, nullptr, nullptr, sm);
+    const bool aligned = (reinterpret_cast<uintptr_t>(values) & 15u) == 0;
+    block_topk(keyfn, n, k, out, nullptr, nullptr, sm, aligned ? values : nullptr);
   }
 }
 

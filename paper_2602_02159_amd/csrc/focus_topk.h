@@ -5,14 +5,15 @@
 // Output: the selected indices in ascending order, then -1 up to k, and the count.
 //
 // Two paths, one workgroup each:
-//   * n <= blockDim : rank by counting — every thread counts how many candidates beat its own, reading the
-//                     staged keys four at a time from LDS (broadcast reads, no dependent chain); the tie rule
-//                     costs extra compares only against the keys of the thread's own wavefront.
+//   * n <= blockDim : the keys are staged in LDS and ONE wavefront, holding up to 16 keys per lane in registers,
+//                     finds the k-th largest key by a 32-step bitwise search over ballot popcounts (no barriers,
+//                     no O(n^2) compares), then emits the selection in index order from ballot prefix counts.
 //   * larger n      : every thread keeps a contiguous run of up to 32 keys in registers (one pass over
-//                     memory); a 4-pass radix select over the 32-bit order-preserving key finds the k-th
-//                     key T and how many keys equal to T are still needed; an ordered compaction then emits
-//                     every key > T and the first needed keys == T in index order.  Runs longer than 32 keys
-//                     per thread re-read memory in every pass.
+//                     memory); a radix select over the 32-bit order-preserving key (8-bit digits, LDS
+//                     histogram; digits in which all keys agree are skipped) finds the k-th key T and how many
+//                     keys equal to T are still needed; an ordered compaction then emits every key > T and the
+//                     first needed keys == T in index order.  Runs longer than 32 keys per thread re-read
+//                     memory in every pass.
 // Both are deterministic: nothing depends on the order in which atomics land.
 #pragma once
 
@@ -28,6 +29,36 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// sum over the n_parts per-head partial values of element j, always in the same order (32 at a time, then 8, then 1)
+// so that every kernel that assembles block relevances gets bit-identical results
+__device__ __forceinline__ float sum_partials(const float* __restrict__ part, int n_parts, int n, int j) {
+  float acc = 0.f;
+  int h = 0;
+  for (; h + 32 <= n_parts; h += 32) {  // 32 independent loads: one memory round trip for 32 heads
+    float v[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) v[u] = part[(int64_t)(h + u) * n + j];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) acc += v[u];
+  }
+  for (; h + 8 <= n_parts; h += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(h + u) * n + j];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; h < n_parts; ++h) acc += part[(int64_t)h * n + j];
+  return acc;
+}
+
+#ifdef FOCUS_TOPK_STAMPS
+__device__ long long g_topk_stamps[32];
+#define TOPK_STAMP(i) do { if (threadIdx.x == 0) g_topk_stamps[i] = clock64(); } while (0)
+#else
+#define TOPK_STAMP(i)
+#endif
+
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkRegKeys = 32;
 
@@ -38,81 +69,120 @@ struct TopkShared {
   uint32_t prefix, remaining;
 };
 
-// Adds one count per active lane to hist[digit].  The lanes that share the first active lane's digit are
-// counted with one ballot and a single atomic, which removes the same-address serialisation when most keys
-// of a wavefront fall into one bin (the common case in the high-order passes).  Wave-uniform control flow.
-__device__ __forceinline__ void wave_hist_add(uint32_t* hist, bool active, uint32_t digit) {
-  const unsigned long long act = __ballot(active);
-  if (act == 0ull) return;
-  const int leader = __ffsll((long long)act) - 1;
-  const uint32_t d0 = __shfl(digit, leader, kWave);
-  const unsigned long long same = __ballot(active && digit == d0);
+// Top-k of up to 64 * KPL keys by ONE wavefront, no barriers.  keys[i] = order key + 1, or 0 for "not a candidate";
+// lane l holds keys[l * KPL .. l * KPL + KPL).  A bitwise search finds T, the k-th largest key (32 steps of KPL
+// compares and ballot popcounts); everything above T is selected, and of the keys equal to T the ones with the
+// lowest indices until k are reached.  Output positions come from ballot prefix counts, so `out` is ascending.
+// Writes out[0..k) (tail -1), flags[0..n) if not null, and *total.  Must be called by all 64 lanes of one wavefront.
+template <int KPL>
+__device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, int32_t* out, uint8_t* flags, uint32_t* total) {
   const int lane = threadIdx.x & 63;
-  if (lane == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-  if (active && digit != d0) atomicAdd(&hist[digit], 1u);
+  uint32_t kv[KPL];
+#pragma unroll
+  for (int r4 = 0; r4 < KPL / 4; ++r4) {
+    const uint4 v = reinterpret_cast<const uint4*>(keys)[lane * (KPL / 4) + r4];
+    kv[4 * r4] = v.x; kv[4 * r4 + 1] = v.y; kv[4 * r4 + 2] = v.z; kv[4 * r4 + 3] = v.w;
+  }
+  uint32_t nvalid = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) nvalid += (uint32_t)__popcll(__ballot(kv[r] != 0u));
+  const uint32_t k_eff = min((uint32_t)max(k, 0), nvalid);
+  uint32_t T = 0;
+  if (k_eff > 0) {
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = T | (1u << bit);
+      uint32_t cnt = 0;
+#pragma unroll
+      for (int r = 0; r < KPL; ++r) cnt += (uint32_t)__popcll(__ballot(kv[r] >= cand));
+      if (cnt >= k_eff) T = cand;
+    }
+  } else {
+    T = 0xffffffffu;
+  }
+  uint32_t n_gt = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) n_gt += (uint32_t)__popcll(__ballot(kv[r] > T));
+  const uint32_t need = k_eff - min(n_gt, k_eff);  // keys equal to T still to take, lowest indices first
+  const unsigned long long below = (1ull << lane) - 1ull;
+  // equal-key rank and output position of this lane's first element: counts over all lower lanes
+  uint32_t eq_before = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) eq_before += (uint32_t)__popcll(__ballot(kv[r] == T) & below);
+  bool sel[KPL];
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const bool eq = kv[r] == T;
+    sel[r] = kv[r] > T || (eq && eq_before < need);
+    eq_before += eq;
+  }
+  uint32_t pos = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) pos += (uint32_t)__popcll(__ballot(sel[r]) & below);
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int idx = lane * KPL + r;
+    if (sel[r]) out[pos++] = idx;
+    if (flags && idx < n) flags[idx] = (uint8_t)sel[r];
+  }
+  for (int i = (int)k_eff + lane; i < k; i += kWave) out[i] = -1;
+  if (lane == 0) *total = k_eff;
 }
 
 // KeyFn: bool operator()(int i, uint32_t& key) const — false when i is not a candidate.
 // Every thread of the workgroup must call this; blockDim.x <= kTopkThreads and a multiple of 64 (>= 256 when
 // n > blockDim.x).  `out` gets k entries, *out_count the number selected.  `flags`, if not null, is
 // workgroup-shared memory of n bytes that receives 1 for selected, 0 otherwise.
+// `dense_values`, if not null, is a 16-byte aligned float array whose element i is the value of candidate i and
+// every i < n is a candidate: the large-n path then fetches each thread's run with 16-byte loads.
 template <class KeyFn>
 __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int32_t* out, int32_t* out_count, uint8_t* flags,
-                           TopkShared& sm) {
+                                           TopkShared& sm, const float* dense_values = nullptr) {
   const int tid = threadIdx.x, nt = blockDim.x;
   uint32_t total;
 
   if (n <= nt) {
-    // ---- rank by counting
+    // ---- small n: keys go to LDS, then ONE wavefront selects (see wave_topk); the others wait at the barrier
     uint32_t mykey = 0;
     const bool myvalid = tid < n && keyfn(tid, mykey);
-    const uint32_t mine = myvalid ? mykey + 1u : 0u;
     __syncthreads();
-    sm.keys[tid] = mine;  // threads past n store 0: never beats anything
+    sm.keys[tid] = myvalid ? mykey + 1u : 0u;  // threads past n store 0: not a candidate
+    for (int i = nt + tid; i < kTopkThreads; i += nt) sm.keys[i] = 0u;
     __syncthreads();
-    // rank = #{j < tid : key_j >= mine} + #{j > tid : key_j > mine}.  Keys are read four at a time; groups that lie
-    // entirely below (above) the index range of this wavefront need one compare and one add per key, only the 16
-    // groups that overlap the wavefront's own indices need the index test.
-    const uint4* k4 = reinterpret_cast<const uint4*>(sm.keys);
-    const int groups = (n + 3) >> 2;
-    const int g_lo = min(__builtin_amdgcn_readfirstlane(tid >> 6) * 16, groups), g_hi = min(g_lo + 16, groups);
-    uint32_t rank = 0;
-#pragma unroll 4
-    for (int j4 = 0; j4 < g_lo; ++j4) {
-      const uint4 v = k4[j4];
-      rank += (v.x >= mine);
-      rank += (v.y >= mine);
-      rank += (v.z >= mine);
-      rank += (v.w >= mine);
+    if (tid < kWave) {
+      if (n <= 256)
+        wave_topk<4>(sm.keys, n, k, out, flags, &sm.prefix);
+      else if (n <= 512)
+        wave_topk<8>(sm.keys, n, k, out, flags, &sm.prefix);
+      else
+        wave_topk<16>(sm.keys, n, k, out, flags, &sm.prefix);
     }
-#pragma unroll 4
-    for (int j4 = g_lo; j4 < g_hi; ++j4) {
-      const uint4 v = k4[j4];
-      const int j = j4 << 2;
-      rank += (v.x > mine) || (v.x == mine && j < tid);
-      rank += (v.y > mine) || (v.y == mine && j + 1 < tid);
-      rank += (v.z > mine) || (v.z == mine && j + 2 < tid);
-      rank += (v.w > mine) || (v.w == mine && j + 3 < tid);
-    }
-#pragma unroll 4
-    for (int j4 = g_hi; j4 < groups; ++j4) {
-      const uint4 v = k4[j4];
-      rank += (v.x > mine);
-      rank += (v.y > mine);
-      rank += (v.z > mine);
-      rank += (v.w > mine);
-    }
-    const bool sel = myvalid && rank < (uint32_t)k;
-    const uint32_t pos = block_flag_scan(sel, sm.wsum, &total);
-    if (sel) out[pos] = tid;
-    if (flags && tid < n) flags[tid] = (uint8_t)sel;
+    __syncthreads();
+    total = sm.prefix;
   } else {
     // ---- radix select; each thread owns the contiguous run [c0, c1)
-    const int chunk = (n + nt - 1) / nt;
+    TOPK_STAMP(0);
+    const int chunk = (((n + nt - 1) / nt) + 3) & ~3;  // a multiple of 4, so runs start 16-byte aligned
     const int c0 = min(tid * chunk, n), c1 = min(c0 + chunk, n);
     const bool in_regs = chunk <= kTopkRegKeys;
     uint32_t rk[kTopkRegKeys];  // key + 1, 0 = not a candidate
-    if (in_regs) {
+    if (in_regs && dense_values != nullptr) {
+#pragma unroll
+      for (int r4 = 0; r4 < kTopkRegKeys / 4; ++r4) {
+        const int i = c0 + 4 * r4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i + 3 < c1) {
+          v = *reinterpret_cast<const float4*>(dense_values + i);
+        } else {
+          if (i < c1) v.x = dense_values[i];
+          if (i + 1 < c1) v.y = dense_values[i + 1];
+          if (i + 2 < c1) v.z = dense_values[i + 2];
+        }
+        rk[4 * r4] = i < c1 ? order_key(v.x) + 1u : 0u;
+        rk[4 * r4 + 1] = i + 1 < c1 ? order_key(v.y) + 1u : 0u;
+        rk[4 * r4 + 2] = i + 2 < c1 ? order_key(v.z) + 1u : 0u;
+        rk[4 * r4 + 3] = i + 3 < c1 ? order_key(v.w) + 1u : 0u;
+      }
+    } else if (in_regs) {
 #pragma unroll
       for (int r = 0; r < kTopkRegKeys; ++r) {
         uint32_t key = 0;
@@ -124,37 +194,79 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       uint32_t key = 0;
       return (c0 + r < c1 && keyfn(c0 + r, key)) ? key + 1u : 0u;
     };
-    uint32_t nvalid_local = 0;
+    TOPK_STAMP(1);
+    // candidates, and the AND / OR of their keys: digits in which every key agrees need no counting pass
+    uint32_t nvalid_local = 0, k_and = 0xffffffffu, k_or = 0u;
+    auto stat = [&](uint32_t key) {
+      if (key != 0u) {
+        ++nvalid_local;
+        k_and &= key;
+        k_or |= key;
+      }
+    };
     if (in_regs) {
 #pragma unroll
-      for (int r = 0; r < kTopkRegKeys; ++r) nvalid_local += rk[r] != 0u;
+      for (int r = 0; r < kTopkRegKeys; ++r) stat(rk[r]);
     } else {
-      for (int r = 0; r < chunk; ++r) nvalid_local += get(r) != 0u;
+      for (int r = 0; r < chunk; ++r) stat(get(r));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      k_and &= __shfl_xor(k_and, o, kWave);
+      k_or |= __shfl_xor(k_or, o, kWave);
+    }
+    if (tid == 0) {
+      sm.hist[0] = 0xffffffffu;
+      sm.hist[1] = 0u;
     }
     uint32_t nvalid;
-    block_exclusive_scan(nvalid_local, sm.wsum, &nvalid);
+    block_exclusive_scan(nvalid_local, sm.wsum, &nvalid);  // contains barriers: hist[0..1] are initialised
+    if ((tid & 63) == 0) {
+      atomicAnd(&sm.hist[0], k_and);
+      atomicOr(&sm.hist[1], k_or);
+    }
+    __syncthreads();
+    const uint32_t all_and = sm.hist[0], varying = sm.hist[0] ^ sm.hist[1];
+    __syncthreads();
+    TOPK_STAMP(2);
     const uint32_t k_eff = min((uint32_t)max(k, 0), nvalid);
     uint32_t T = 0xffffffffu, need = 0;  // on key + 1; k_eff == 0: nothing is > T and nothing is needed
     if (k_eff > 0) {
       uint32_t prefix = 0, maskbits = 0, remaining = k_eff;
       for (int shift = 24; shift >= 0; shift -= 8) {
+        if (((varying >> shift) & 0xffu) == 0u) {  // every candidate has the same digit here (uniform branch)
+          prefix |= all_and & (0xffu << shift);
+          maskbits |= 0xffu << shift;
+          continue;
+        }
+        TOPK_STAMP(3 + (24 - shift) / 8 * 2);
         if (tid < 256) sm.hist[tid] = 0;
         __syncthreads();
-        if (in_regs) {
-#pragma unroll
-          for (int r = 0; r < kTopkRegKeys; ++r) {
-            if (r < chunk) {  // uniform
-              const uint32_t key = rk[r];
-              wave_hist_add(sm.hist, key != 0u && (key & maskbits) == prefix, (key >> shift) & 255u);
+        // Histogram of this digit over the thread's run.  Equal digits that follow each other are merged into one
+        // atomic: column masses and similar keys fall into one or two bins in the high-order passes, and 32768
+        // atomics on one LDS word would serialise.
+        uint32_t cur = 0xffffffffu, run = 0;
+        auto count = [&](uint32_t key) {
+          if (key != 0u && (key & maskbits) == prefix) {
+            const uint32_t d = (key >> shift) & 255u;
+            if (d == cur) {
+              ++run;
+            } else {
+              if (run) atomicAdd(&sm.hist[cur], run);
+              cur = d;
+              run = 1;
             }
           }
+        };
+        if (in_regs) {
+#pragma unroll
+          for (int r = 0; r < kTopkRegKeys; ++r) count(rk[r]);
         } else {
-          for (int r = 0; r < chunk; ++r) {
-            const uint32_t key = get(r);
-            wave_hist_add(sm.hist, key != 0u && (key & maskbits) == prefix, (key >> shift) & 255u);
-          }
+          for (int r = 0; r < chunk; ++r) count(get(r));
         }
+        if (run) atomicAdd(&sm.hist[cur], run);
         __syncthreads();
+        TOPK_STAMP(4 + (24 - shift) / 8 * 2);
         // suffix counts over the 256 digits: above[d] = number of matching keys whose digit exceeds d
         uint32_t mine = 0, incl = 0;
         if (tid < 256) {
@@ -186,6 +298,7 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       T = prefix;
       need = remaining;
     }
+    TOPK_STAMP(11);
     // ---- ordered compaction
     uint32_t cg = 0, ce = 0;
     if (in_regs) {
@@ -219,14 +332,17 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       }
       if (flags && c0 + r < c1) flags[c0 + r] = (uint8_t)sel;
     };
-    if (in_regs) {
+    if (flags != nullptr || cg + ce != 0u) {  // most runs hold nothing to emit when k << n
+      if (in_regs) {
 #pragma unroll
-      for (int r = 0; r < kTopkRegKeys; ++r)
-        if (r < chunk) emit(r, rk[r]);
-    } else {
-      for (int r = 0; r < chunk; ++r) emit(r, get(r));
+        for (int r = 0; r < kTopkRegKeys; ++r)
+          if (r < chunk) emit(r, rk[r]);
+      } else {
+        for (int r = 0; r < chunk; ++r) emit(r, get(r));
+      }
     }
     total = tg + min(te, need);
+    TOPK_STAMP(12);
   }
   for (int i = (int)total + tid; i < k; i += nt) out[i] = -1;
   if (tid == 0 && out_count) *out_count = (int32_t)total;

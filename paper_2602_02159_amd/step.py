@@ -61,8 +61,9 @@ class FocusStep:
                                                  C.byref(s_probe), n_sink, p(self.col_mass), p(self.sink_idx), p(ws_sinks),
                                                  ws_sinks.numel()))],
             "block_means": [], "block_scores": [], "block_scores_cached": [], "sparse_attn": [], "dense_attn": [],
+            "sparse_layer": [], "sparse_layer_cached": [],
         }
-        ws_scores = ws_attn = ws_dense = None
+        ws_scores = ws_attn = ws_dense = ws_layer = None
         for (q, k, v), b in zip(self.layers, self.bufs):
             s = fb.make_shape(q, k, v, n_ctx, block, b["out"])
             self._keep.append(s)
@@ -71,6 +72,7 @@ class FocusStep:
                 ws_scores = workspace(fb.workspace_bytes(fb.FN_BLOCK_SCORES, s))
                 ws_attn = workspace(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, self.max_active, n_keep, n_sink))
                 ws_dense = workspace(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, self.max_active, self.n_b, 0))
+                ws_layer = workspace(fb.workspace_bytes(fb.FN_SPARSE_LAYER, s, self.max_active, n_keep, n_sink))
             self.calls["block_means"].append((L.focus_block_means, (p(k), sp, p(b["kbar"]))))
             self.calls["block_scores"].append((L.focus_block_scores, (
                 p(q), p(self.focus_idx), p(self.counts), k_focus, p(k), None, sp, n_keep, p(b["scores"]), p(b["kept"]),
@@ -81,10 +83,15 @@ class FocusStep:
             self.calls["sparse_attn"].append((L.focus_sparse_attn, (
                 p(q), p(self.active_idx), p(self.counts), self.max_active, p(k), p(v), sp, p(b["kept"]), n_keep,
                 p(self.sink_idx), n_sink, p(b["out"]), None, p(ws_attn), ws_attn.numel())))
+            for stage, kb in (("sparse_layer", None), ("sparse_layer_cached", p(b["kbar"]))):
+                self.calls[stage].append((L.focus_sparse_layer, (
+                    p(q), p(self.focus_idx), p(self.active_idx), p(self.counts), k_focus, self.max_active, p(k), p(v), kb, sp,
+                    n_keep, p(self.sink_idx), n_sink, p(b["scores"]), p(b["kept"]), p(b["out"]), None, p(ws_layer),
+                    ws_layer.numel())))
             self.calls["dense_attn"].append((L.focus_sparse_attn, (
                 p(q), p(self.active_idx), p(self.counts), self.max_active, p(k), p(v), sp, p(self.all_blocks), self.n_b,
                 None, 0, p(b["out"]), None, p(ws_dense), ws_dense.numel())))
-        self.cached_means, self.dense = cached_means, dense
+        self.cached_means, self.dense, self.fused = cached_means, dense, True
         self._graph = None
 
     @staticmethod
@@ -102,12 +109,13 @@ class FocusStep:
     def sequence(self):
         """The step's calls in order: queries once, sinks once at the probe layer, then every sparse layer."""
         seq = self.calls["select"] + self.calls["find_sinks"]
+        if self.dense:
+            return seq + self.calls["dense_attn"]
+        if self.fused:  # one call per sparse layer: block scores and attention in three launches
+            return seq + self.calls["sparse_layer_cached" if self.cached_means else "sparse_layer"]
         scores = self.calls["block_scores_cached" if self.cached_means else "block_scores"]
-        attn = self.calls["dense_attn" if self.dense else "sparse_attn"]
         for i in range(len(self.layers)):
-            if not self.dense:
-                seq = seq + [scores[i]]
-            seq = seq + [attn[i]]
+            seq = seq + [scores[i], self.calls["sparse_attn"][i]]
         return seq
 
     def run(self):

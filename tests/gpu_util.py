@@ -99,3 +99,20 @@ def assert_attention_close(out_gpu: torch.Tensor, out_ref: np.ndarray, max_abs=2
 
 def oracle_layer(q, k, v, focus, active, sinks, n_ctx, block, n_keep):
     return fo.focus_layer(to_np(q), to_np(k), to_np(v), focus, active, sinks, n_ctx, block, n_keep)
+
+
+def gpu_sparse_layer(q, focus, active, counts, k, v, kbar, n_ctx, block, n_keep, sinks):
+    H, _, d = q.shape
+    n_sink = 0 if sinks is None else sinks.numel()
+    n_b = -(-n_ctx // block)
+    max_active = active.numel()
+    out = torch.full((H, max_active, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((H, max_active), float("nan"), dtype=torch.float32, device=DEV)
+    scores = torch.full((n_b,), float("nan"), dtype=torch.float32, device=DEV)
+    kept = i32(None, max(n_keep, 1))
+    s = fb.make_shape(q, k, v, n_ctx, block, out)
+    w = ws(fb.workspace_bytes(fb.FN_SPARSE_LAYER, s, max_active, n_keep, n_sink))
+    w.fill_(0xAB)   # the call must not rely on a cleared workspace
+    fb.sparse_layer(q, focus, active, counts, k, v, kbar, s, n_keep, sinks if n_sink else None, n_sink, scores, kept, out, lse, w)
+    torch.cuda.synchronize()
+    return scores, kept[:n_keep], out, lse

@@ -243,8 +243,38 @@ def test_sparse_attn_is_deterministic_and_linear_in_v(G):
     assert torch.equal(o3.float(), o1.float() * 2)         # scaling by two is exact in bf16
 
 
+# ------------------------------------------------------------------------------------------------ fused layer call
+@pytest.mark.parametrize("H,M,N,d,B,n_gen,n_f,n_act,n_keep,n_sink", [
+    (4, 1024, 32, 64, 64, 32, 8, 8, 4, 2),
+    (8, 4096, 64, 128, 128, 64, 16, 16, 5, 4),        # 32 blocks, several splits per head
+    (3, 3000, 40, 128, 48, 48, 5, 40, 9, 7),          # ragged, three query tiles
+    (2, 16384, 64, 128, 64, 64, 16, 16, 25, 4),       # exactly 256 blocks: the largest fused case
+    (2, 8192, 64, 128, 16, 64, 16, 16, 40, 4),        # 512 blocks: falls back to the separate kernels
+    (2, 2048, 0, 64, 128, 16, 3, 16, 16, 0),          # every block kept, no response rows, no sinks
+])
+def test_sparse_layer_equals_block_scores_then_sparse_attn(G, H, M, N, d, B, n_gen, n_f, n_act, n_keep, n_sink):
+    rng = np.random.default_rng(M + n_keep)
+    q, k, v = (_rand_bf16(61 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    focus = G.i32(np.sort(rng.choice(n_gen, n_f, replace=False)))
+    active = G.i32(np.sort(rng.choice(n_gen, n_act, replace=False)))
+    sinks = G.i32(rng.choice(M, n_sink, replace=False)) if n_sink else None
+    counts = G.i32([n_f, n_act])
+    scores, kept = G.gpu_block_scores(q, focus, counts, k, None, M, B, n_keep)
+    out, lse = G.gpu_sparse_attn(q, active, counts, k, v, M, B, kept, sinks)
+    for kbar in (None, G.gpu_block_means(k, M, B)):
+        for _ in range(2):                                  # twice: arrival counters must be reusable
+            s2, k2, o2, l2 = G.gpu_sparse_layer(q, focus, active, counts, k, v, kbar, M, B, n_keep, sinks)
+            assert torch.equal(s2, scores) and torch.equal(k2, kept)
+            assert torch.equal(o2, out) and torch.equal(l2, lse)
+    # and against the oracle
+    lay = fo.focus_layer(G.to_np(q), G.to_np(k), G.to_np(v), focus.cpu().numpy(), active.cpu().numpy(),
+                         [] if sinks is None else sinks.cpu().numpy(), M, B, n_keep)
+    assert kept.cpu().tolist() == lay["blocks"].tolist()
+    G.assert_attention_close(out, lay["out"])
+
+
 # ------------------------------------------------------------------------------------------------ whole layer on the workloads
-@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx16k", "ctx32k"])
+@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx16k", "ctx32k", "paper32k"])
 def test_workload_layer_end_to_end(G, name):
     w = fi.WORKLOADS[name]
     q, k, v = (t.to(G.DEV) for t in fi.layer_qkv(w, 0))
@@ -256,26 +286,33 @@ def test_workload_layer_end_to_end(G, name):
     S_ref = fo.sink_scores(Q, active_ref, K)
     sinks_ref = fo.select_sinks(S_ref, w.n_ctx, w.n_sink)
     lay = fo.focus_layer(Q, K, V, focus_ref, active_ref, sinks_ref, w.n_ctx, w.block, w.n_keep)
-    assert fo.decision_margin(S_ref, w.n_sink, np.arange(w.n_kv) < w.n_ctx) > 1e-4
-    assert fo.decision_margin(lay["R"], w.n_keep) > 1e-4
+    # index parity is only well posed away from near-ties; fp32 reordering noise is below 1e-6 of the score spread
+    min_margin = 1e-5 if name == "paper32k" else 1e-4      # selecting hundreds of items leaves smaller gaps
+    assert fo.decision_margin(S_ref, w.n_sink, np.arange(w.n_kv) < w.n_ctx) > min_margin
+    assert fo.decision_margin(lay["R"], w.n_keep) > min_margin
     # device, chained without host round trips of the index sets
     focus, active, counts = G.gpu_select(conf.numpy(), fi.masked_all(w).numpy(), w.k_focus, w.window, 0, w.n_gen)
     col, sinks = G.gpu_find_sinks(q, active, counts, k, w.n_ctx, w.block, w.n_sink)
     scores, kept = G.gpu_block_scores(q, focus, counts, k, None, w.n_ctx, w.block, w.n_keep)
     out, lse = G.gpu_sparse_attn(q, active, counts, k, v, w.n_ctx, w.block, kept, sinks)
+    n_q = len(active_ref)
+    assert counts.cpu().tolist() == [len(focus_ref), n_q]
     assert focus.cpu().tolist() == focus_ref.tolist()
-    assert active.cpu().tolist() == active_ref.tolist()
+    assert active.cpu().tolist() == active_ref.tolist() + [-1] * (active.numel() - n_q)
     assert sinks.cpu().tolist() == sinks_ref.tolist()
     assert kept.cpu().tolist() == lay["blocks"].tolist()
     assert np.allclose(col.cpu().numpy(), S_ref, rtol=2e-4, atol=1e-10)
     assert np.allclose(scores.cpu().numpy(), lay["R"], atol=2e-6)
-    G.assert_attention_close(out, lay["out"])
-    assert np.allclose(lse.cpu().numpy(), lay["lse"], atol=2e-3)
+    G.assert_attention_close(out[:, :n_q], lay["out"])
+    assert np.allclose(lse.cpu().numpy()[:, :n_q], lay["lse"], atol=2e-3)
+    # the fused per-layer call gives the same bits as the two separate calls
+    s2, k2, o2, _ = G.gpu_sparse_layer(q, focus, active, counts, k, v, None, w.n_ctx, w.block, w.n_keep, sinks)
+    assert torch.equal(s2, scores) and torch.equal(k2, kept) and torch.equal(o2[:, :n_q], out[:, :n_q])
     # dense comparison baseline through the same entry point: every block kept
     n_b = w.n_blocks
     dense, _ = G.gpu_sparse_attn(q, active, counts, k, v, w.n_ctx, w.block, G.i32(np.arange(n_b)), None)
     I_all = fo.attention_index_set([], np.arange(n_b), w.n_ctx, w.block)
-    G.assert_attention_close(dense, fo.sparse_attention(Q, active_ref, K, V, I_all, w.n_ctx)[0])
+    G.assert_attention_close(dense[:, :n_q], fo.sparse_attention(Q, active_ref, K, V, I_all, w.n_ctx)[0])
 
 
 def test_stack_reuses_probe_layer_sinks(G):
