@@ -62,6 +62,9 @@ __device__ __forceinline__ int stage_off(int row, int chunk) {
   return row * Geo<D>::kRowBytes + ((chunk ^ (row & (Geo<D>::kChunks - 1))) << 4);
 }
 
+// cache policy of the K/V row loads: non-temporal (every row is read once per launch)
+constexpr int kStreamPolicy = 2;
+
 // s_waitcnt vmcnt(0): every outstanding global load, LDS-direct ones included, has landed
 __device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
@@ -159,7 +162,7 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
     }
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
-    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, kStreamPolicy);
   }
 }
 
