@@ -158,7 +158,7 @@ def main() -> int:
         st = steps_obj[0]
         st.run()
         sync()
-        for stage in ("block_means", "block_scores_cached", "sparse_attn", "dense_attn", "find_sinks", "select"):
+        for stage in ("block_means", "block_partials", "block_scores_cached", "sparse_attn", "dense_attn", "find_sinks", "select"):
             st.issue(stage)
             sync()
         print(json.dumps({"mode": "pmc", "copy_bytes": int(src.numel() * 4), "workload": w.name}))
@@ -187,12 +187,13 @@ def main() -> int:
         "select": {"bytes": w.n_gen * 5 + 4 * (w.k_focus + n_q + 2), "flops": 0},
         "find_sinks": {"bytes": L * H * d * 2 + n_q * H * d * 2 + L * 4, "flops": 2 * n_q * L * d * H},
         "block_means": {"bytes": M * H * d * 2 + n_b * H * d * 4, "flops": M * H * d},
+        "block_partials": {"bytes": M * H * d * 2 + w.k_focus * H * d * 2 + n_b * H * 4, "flops": M * H * d + 2 * n_b * d * H},
         "block_scores_cached": {"bytes": n_b * H * d * 4 + w.k_focus * H * d * 2 + n_b * 4, "flops": 2 * n_b * d * H},
         "sparse_attn": {"bytes": 2 * mean_keys * H * d * 2 + 2 * n_q * H * d * 2, "flops": 4 * n_q * mean_keys * d * H},
         "dense_attn": {"bytes": 2 * L * H * d * 2 + 2 * n_q * H * d * 2, "flops": 4 * n_q * L * d * H},
     }
-    alg["block_scores"] = {"bytes": alg["block_means"]["bytes"] + alg["block_scores_cached"]["bytes"],
-                           "flops": alg["block_means"]["flops"] + alg["block_scores_cached"]["flops"]}
+    # scoring from raw K: the scan emits the per-head partial relevances directly (no means are stored), then Top-C
+    alg["block_scores"] = {"bytes": alg["block_partials"]["bytes"] + n_b * H * 4 + n_b * 4, "flops": alg["block_partials"]["flops"]}
     alg["sparse_layer_cached"] = {"bytes": alg["block_scores_cached"]["bytes"] + alg["sparse_attn"]["bytes"],
                                   "flops": alg["block_scores_cached"]["flops"] + alg["sparse_attn"]["flops"]}
     alg["sparse_layer"] = {"bytes": alg["block_scores"]["bytes"] + alg["sparse_attn"]["bytes"],
@@ -271,10 +272,10 @@ def main() -> int:
         return e0.elapsed_time(e1) * 1e3 / n_launch  # microseconds per launch
 
     stages = {}
-    per_step_count = {"select": 1, "find_sinks": 1, "block_means": n_sparse, "block_scores_cached": n_sparse,
+    per_step_count = {"select": 1, "find_sinks": 1, "block_means": n_sparse, "block_partials": n_sparse, "block_scores_cached": n_sparse,
                       "block_scores": n_sparse, "sparse_attn": n_sparse, "dense_attn": n_sparse, "sparse_layer": n_sparse,
                       "sparse_layer_cached": n_sparse}
-    for stage in ("select", "find_sinks", "block_means", "block_scores_cached", "block_scores", "sparse_attn", "dense_attn",
+    for stage in ("select", "find_sinks", "block_means", "block_partials", "block_scores_cached", "block_scores", "sparse_attn", "dense_attn",
                   "sparse_layer_cached", "sparse_layer"):
         us = time_stage(stage)
         a = alg[stage]
@@ -285,22 +286,24 @@ def main() -> int:
 
     # the stage that takes the largest share of the timed step
     # (the step calls focus_sparse_layer; its parts are also timed through the separate entry points, which run the same kernels)
-    in_step = ("select", "find_sinks", "block_means", "sparse_layer_cached")
+    in_step = ("select", "find_sinks", "block_partials", "sparse_attn")
     share = {s: stages[s]["us_per_launch"] * per_step_count[s] for s in in_step}
-    dom = max(share, key=share.get)
-    dom_kernel = {"block_means": "block_means", "find_sinks": "find_sinks", "sparse_layer_cached": "sparse_attn", "select": "select"}[dom]
+    dom_kernel = max(share, key=share.get)
     ds = stages[dom_kernel]
-    kernel_name = {"block_means": "block_means_kernel<128>", "find_sinks": "qk_logits_kernel<128, 1>",
-                   "sparse_attn": "sparse_attn_kernel<128, 1>", "select": "select_queries_kernel"}[dom_kernel]
+    kernel_name = {"block_partials": "block_means_kernel<128, true>", "find_sinks": "qk_logits_kernel<128, 1>",
+                   "sparse_attn": "sparse_attn_kernel<128, 1, 1>", "select": "select_queries_kernel"}[dom_kernel]
     # HBM traffic of that kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in a separate run of this
     # script (--mode pmc) and stored by --parse-pmc; scaled by the counters' reading for a 1 GiB copy
     traffic = None
     try:
         with open(PMC_FILE.format(w.name)) as fh:
             pmc = json.load(fh)
+        # the counters are taken on the stand-alone stages; the attention kernel appears there without the fused Top-C
+        # prologue (<128, 1, 0>), a name the dense comparison shares: its smallest dispatch is the sparse one
+        want = "sparse_attn_kernel<128, 1, 0>" if dom_kernel == "sparse_attn" else kernel_name
+        which = "min" if dom_kernel == "sparse_attn" else "max"
         for name, v in pmc["kernels"].items():
-            if kernel_name.split("<")[0] in name:
-                which = "min" if dom_kernel == "sparse_attn" else "max"   # the dense comparison shares the kernel's name
+            if want in name:
                 traffic = int(v[f"fetch_bytes_{which}"] + v[f"write_bytes_{which}"])
     except (OSError, KeyError, ValueError):
         pass
@@ -310,7 +313,7 @@ def main() -> int:
 
     step_bytes = alg["select"]["bytes"] + alg["find_sinks"]["bytes"] + n_sparse * (alg["block_scores"]["bytes"] + alg["sparse_attn"]["bytes"])
     step_flops = alg["find_sinks"]["flops"] + n_sparse * (alg["block_scores"]["flops"] + alg["sparse_attn"]["flops"])
-    cached_bytes = step_bytes - n_sparse * alg["block_means"]["bytes"]
+    cached_bytes = alg["select"]["bytes"] + alg["find_sinks"]["bytes"] + n_sparse * alg["sparse_layer_cached"]["bytes"]
 
     # ---- parity spot check + CPU baseline: the oracle on the probe layer and the first sparse layers of set 0
     cpu = None
@@ -359,7 +362,7 @@ def main() -> int:
                    "heads": H, "head_dim": d, "n_ctx": M, "n_resp": w.n_resp, "block": w.block, "n_queries": n_q,
                    "n_keep": w.n_keep, "n_sink": w.n_sink, "mean_keys_attended": mean_keys, "launch": "hip_graph" if use_graph else "eager",
                    "input_sets_rotated": args.sets, "block_means": "recomputed every step",
-                   "per_layer_call": "focus_sparse_layer (block scores + attention in three launches)"},
+                   "per_layer_call": "focus_sparse_layer (K scan -> partial relevances, attention with Top-C inside, combine: three launches)"},
         "achieved_hbm_GBps": round(step_bytes / ms_step * 1e-6, 1), "achieved_TFLOPps": round(step_flops / ms_step * 1e-9, 3),
         "step_hbm_frac": round(step_bytes / ms_step * 1e-6 / HBM_PEAK_GBS, 4),
         "ms_per_step_block_means_cached": round(ms_cached, 4),

@@ -101,8 +101,8 @@ int focus_block_means(const void* K, const focus_shape* shape, float* kbar, void
  *   R_b = (1/H) sum_h qbar^h . kbar^h_b,  qbar^h = mean over I_focus of Q[h, i, :]   (fp32 throughout)
  *   Q          [dev] bf16 [H, n_gen, d]
  *   focus_idx  [dev] int32[n_focus_max] rows of Q; counts[0] (or n_focus_max if counts is NULL) are valid
- *   kbar       [dev] fp32 [H, n_b, d] from focus_block_means, or NULL: then K [dev] is scanned first and the
- *              means are built in the workspace (K may be NULL when kbar is given)
+ *   kbar       [dev] fp32 [H, n_b, d] from focus_block_means, or NULL: then K [dev] is scanned instead and each
+ *              block's mean is formed and consumed on the fly, bit-identically (K may be NULL when kbar is given)
  *   n_keep     C, 0 <= C <= n_b (pass floor(alpha * n_b) — see focus_helper_n_keep)
  *   scores     [dev] fp32[n_b] out, may be NULL
  *   kept_blocks[dev] int32[n_keep] out, ascending block ids
@@ -110,6 +110,21 @@ int focus_block_means(const void* K, const focus_shape* shape, float* kbar, void
 int focus_block_scores(const void* Q, const int32_t* focus_idx, const int32_t* counts, int32_t n_focus_max,
                        const void* K, const float* kbar, const focus_shape* shape, int32_t n_keep, float* scores,
                        int32_t* kept_blocks, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * The two halves of focus_block_scores, for callers that hold only a slice of the heads (head-sharded layers sum
+ * the partials of all slices before ranking) and for timing the K scan on its own.
+ *   focus_block_partials:  partials[h, b] = sum over I_focus of Q[h, i, :] . kbar^h_b     fp32 [H, n_b] out
+ *                          (the un-normalised per-head term of Eq. 7; kbar / K as in focus_block_scores)
+ *   focus_top_blocks:      R_b = (sum over the n_parts rows of partials[:, b]) / (|I_focus| * n_parts), summed in a
+ *                          fixed order, then B_relevant = Top-C of R (Sec. 5.3).  partials fp32 [n_parts, n_blocks],
+ *                          1 <= n_parts <= 1024; scores fp32[n_blocks] out (required); kept_blocks as above.
+ * focus_block_scores(...) == focus_block_partials(...) into its workspace, then focus_top_blocks(n_parts = H).
+ */
+int focus_block_partials(const void* Q, const int32_t* focus_idx, const int32_t* counts, int32_t n_focus_max,
+                         const void* K, const float* kbar, const focus_shape* shape, float* partials, void* stream);
+int focus_top_blocks(const float* partials, int32_t n_parts, const int32_t* counts, int32_t n_focus_max,
+                     int32_t n_blocks, int32_t n_keep, float* scores, int32_t* kept_blocks, void* stream);
 
 /*
  * Dynamic attention-sink identification at the probe layer (Sec. 5.3, Eq. 6).
@@ -149,7 +164,7 @@ int focus_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* c
  * attention (Eq. 9) — exactly focus_block_scores followed by focus_sparse_attn, with the same arguments and
  * bit-identical outputs (scores, kept_blocks, out, lse), but in three kernel launches instead of four: the
  * attention kernel ranks the blocks itself from the per-head partial relevances instead of waiting for a
- * separate Top-C kernel.  kbar NULL: the block means are built from K first (one more launch).
+ * separate Top-C kernel.  kbar NULL: the first launch scans K and forms the block means on the fly.
  * With more than 256 prompt blocks the call falls back to the separate kernels.
  */
 int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* active_idx, const int32_t* counts,

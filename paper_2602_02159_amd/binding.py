@@ -19,7 +19,7 @@ FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0,
 FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER = 1, 2, 3, 4
 
 EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
-           "focus_sparse_layer",
+           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
 
@@ -56,8 +56,10 @@ def lib() -> C.CDLL:
         L.focus_find_sinks.argtypes = [p, p, p, i32, p, sp, i32, p, p, p, sz, p]
         L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
+        L.focus_block_partials.argtypes = [p, p, p, i32, p, p, sp, p, p]
+        L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
-                     "focus_sparse_attn", "focus_sparse_layer"):
+                     "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
         L.focus_workspace_bytes.restype = sz
@@ -145,6 +147,20 @@ def block_scores(q, focus_idx, counts, k, kbar, shape: Shape, n_keep: int, score
     _check(lib().focus_block_scores(_ptr(q), _ptr(focus_idx), _ptr(counts), focus_idx.numel(), _ptr(k), _ptr(kbar),
                                     C.byref(shape), n_keep, _ptr(scores), _ptr(kept_blocks), _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def block_partials(q, focus_idx, counts, k, kbar, shape: Shape, partials) -> None:
+    _need(q, torch.bfloat16, "Q")
+    _need(partials, torch.float32, "partials")
+    _check(lib().focus_block_partials(_ptr(q), _ptr(focus_idx), _ptr(counts), focus_idx.numel(), _ptr(k), _ptr(kbar),
+                                      C.byref(shape), _ptr(partials), _stream()))
+
+
+def top_blocks(partials, counts, n_focus_max: int, n_keep: int, scores, kept_blocks) -> None:
+    _need(partials, torch.float32, "partials")
+    n_parts, n_blocks = partials.shape
+    _check(lib().focus_top_blocks(_ptr(partials), n_parts, _ptr(counts), n_focus_max, n_blocks, n_keep, _ptr(scores),
+                                  _ptr(kept_blocks), _stream()))
 
 
 def find_sinks(q, active_idx, counts, k, shape: Shape, n_sink: int, col_mass, sink_idx, workspace) -> None:

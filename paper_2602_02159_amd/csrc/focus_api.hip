@@ -86,13 +86,12 @@ static int check_shape(const focus_shape* s, bool need_q, bool need_k, bool need
 }
 
 struct ScoreWs {
-  size_t kbar, part, scores, total;
+  size_t part, scores, total;
 };
 static ScoreWs ws_block_scores(const focus_shape& s) {
   const size_t n_b = ceil_div(s.n_ctx, s.block);
   ScoreWs w;
-  w.kbar = 0;
-  w.part = align_up((size_t)s.n_heads * n_b * s.head_dim * sizeof(float));
+  w.part = 0;
   w.scores = w.part + align_up((size_t)s.n_heads * n_b * sizeof(float));
   w.total = w.scores + align_up(n_b * sizeof(float));
   return w;
@@ -224,19 +223,45 @@ int focus_block_scores(const void* Q, const int32_t* focus_idx, const int32_t* c
     return fail(FOCUS_EWORKSPACE, "focus_block_scores: workspace needs %zu bytes, 16-byte aligned", w.total);
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  float* ws_kbar = reinterpret_cast<float*>(ws + w.kbar);
   float* part = reinterpret_cast<float*>(ws + w.part);
   float* R = scores ? scores : reinterpret_cast<float*>(ws + w.scores);
   hipError_t e;
-  if (!kbar) {
-    e = launch_block_means(K, *shape, ws_kbar, st);
-    if (e != hipSuccess) return launch_fail("focus_block_scores(block means)", e);
-    kbar = ws_kbar;
-  }
-  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
+  if (!kbar)  // one scan of K gives the partial relevances directly; the means are not materialised
+    e = launch_block_means_relevance(K, Q, focus_idx, counts, n_focus_max, *shape, nullptr, part, st);
+  else
+    e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
   if (e != hipSuccess) return launch_fail("focus_block_scores(relevance)", e);
   e = launch_reduce_topk(part, shape->n_heads, counts, n_focus_max, R, n_b, n_keep, kept_blocks, st);
   if (e != hipSuccess) return launch_fail("focus_block_scores(top-C)", e);
+  return FOCUS_OK;
+}
+
+int focus_block_partials(const void* Q, const int32_t* focus_idx, const int32_t* counts, int32_t n_focus_max, const void* K,
+                         const float* kbar, const focus_shape* shape, float* partials, void* stream) {
+  if (int rc = check_shape(shape, true, kbar == nullptr, false, false)) return rc;
+  if (!Q || !focus_idx || !partials) return fail(FOCUS_EINVAL, "focus_block_partials: NULL pointer");
+  if (!kbar && !K) return fail(FOCUS_EINVAL, "focus_block_partials: both kbar and K are NULL");
+  if (n_focus_max < 1 || n_focus_max > shape->n_gen) return fail(FOCUS_EINVAL, "focus_block_partials: n_focus_max=%d not in [1, n_gen]", n_focus_max);
+  if (!aligned16(Q) || (kbar && !aligned16(kbar)) || (!kbar && !aligned16(K)))
+    return fail(FOCUS_EINVAL, "focus_block_partials: pointers must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = kbar ? launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, partials, st)
+                      : launch_block_means_relevance(K, Q, focus_idx, counts, n_focus_max, *shape, nullptr, partials, st);
+  if (e != hipSuccess) return launch_fail("focus_block_partials", e);
+  return FOCUS_OK;
+}
+
+int focus_top_blocks(const float* partials, int32_t n_parts, const int32_t* counts, int32_t n_focus_max, int32_t n_blocks,
+                     int32_t n_keep, float* scores, int32_t* kept_blocks, void* stream) {
+  if (!partials || !scores) return fail(FOCUS_EINVAL, "focus_top_blocks: NULL pointer");
+  if (n_parts < 1 || n_parts > 1024) return fail(FOCUS_EINVAL, "focus_top_blocks: n_parts=%d not in [1, 1024]", n_parts);
+  if (n_blocks < 1) return fail(FOCUS_EINVAL, "focus_top_blocks: n_blocks=%d", n_blocks);
+  if (n_focus_max < 1) return fail(FOCUS_EINVAL, "focus_top_blocks: n_focus_max=%d", n_focus_max);
+  if (n_keep < 0 || n_keep > n_blocks) return fail(FOCUS_EINVAL, "focus_top_blocks: n_keep=%d not in [0, n_blocks=%d]", n_keep, n_blocks);
+  if (n_keep > 0 && !kept_blocks) return fail(FOCUS_EINVAL, "focus_top_blocks: kept_blocks is NULL");
+  hipError_t e = launch_reduce_topk(partials, n_parts, counts, n_focus_max, scores, n_blocks, n_keep, kept_blocks,
+                                    static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_top_blocks", e);
   return FOCUS_OK;
 }
 
@@ -319,19 +344,16 @@ int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* a
     return fail(FOCUS_EWORKSPACE, "focus_sparse_layer: workspace needs %zu bytes, 16-byte aligned", w.total);
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  float* ws_kbar = reinterpret_cast<float*>(ws + w.sc.kbar);
   float* part = reinterpret_cast<float*>(ws + w.sc.part);
   float* R = scores ? scores : reinterpret_cast<float*>(ws + w.sc.scores);
   float* part_o = reinterpret_cast<float*>(ws + w.attn + w.at.part_o);
   float* part_ml = reinterpret_cast<float*>(ws + w.attn + w.at.part_ml);
   hipError_t e;
-  if (!kbar) {
-    e = launch_block_means(K, *shape, ws_kbar, st);
-    if (e != hipSuccess) return launch_fail("focus_sparse_layer(block means)", e);
-    kbar = ws_kbar;
-  }
   const bool fused = n_b <= kFusedMaxBlocks && n_keep > 0;
-  e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
+  if (!kbar)
+    e = launch_block_means_relevance(K, Q, focus_idx, counts, n_focus_max, *shape, nullptr, part, st);
+  else
+    e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
   if (e != hipSuccess) return launch_fail("focus_sparse_layer(relevance)", e);
   if (fused) {
     FusedTopC f;

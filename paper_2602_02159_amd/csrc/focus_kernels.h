@@ -33,6 +33,9 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
                                  int hi, int32_t* focus_idx, int32_t* active_idx, int max_active, int32_t* counts,
                                  hipStream_t st);
 hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, hipStream_t st);
+// one scan of K that yields the per-head partial relevances (and, if kbar is not null, the block means)
+hipError_t launch_block_means_relevance(const void* K, const void* Q, const int32_t* focus_idx, const int32_t* counts,
+                                        int n_focus_max, const focus_shape& s, float* kbar, float* part, hipStream_t st);
 // per-head partial relevances part[H, n_b] (sum over the focus queries, not yet scaled)
 hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const int32_t* counts, int n_focus_max,
                                   const float* kbar, const focus_shape& s, float* part, hipStream_t st);

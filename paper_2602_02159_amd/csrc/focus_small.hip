@@ -114,21 +114,95 @@ hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* cou
 }
 
 // =====================================================================================================
+// Helpers shared by the block-relevance kernels, written once so that the K-scanning and the cached-means
+// variants produce bit-identical partial relevances.
+// =====================================================================================================
+// Sum over the focus queries of Q[h, i, 8c .. 8c+7] for the calling thread's chunk c = t % (D/8).  All 256 threads
+// take part: thread (r, c) adds up the focus rows r, r + RPP, r + 2 RPP, ... (four loads in flight at a time), the
+// per-r sums meet in LDS and every thread then adds them in the order r = 0 .. RPP-1.  `first_row` is
+// focus_idx[r] fetched by the caller ahead of time (any value if r >= n_focus_max); `psum` must be free on entry.
+template <int D>
+__device__ __forceinline__ void focus_row_sum(float (&qs)[8], const uint16_t* __restrict__ qh, int64_t qsn,
+                                              const int32_t* __restrict__ focus_idx, int first_row, int n_f, int n_gen,
+                                              float (*psum)[D]) {
+  constexpr int CPR = D / 8, RPP = 256 / CPR, U = 4;
+  const int c = threadIdx.x % CPR, r = threadIdx.x / CPR;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int f0 = r; f0 < n_f; f0 += RPP * U) {
+    int rows[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int f = f0 + u * RPP;
+      rows[u] = f < n_f ? (f == r ? first_row : focus_idx[f]) : -1;
+    }
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      v[u] = (rows[u] >= 0 && rows[u] < n_gen) ? *reinterpret_cast<const uint4*>(qh + (int64_t)rows[u] * qsn + c * 8)
+                                                : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int u = 0; u < U; ++u) add_bf16x8(acc, v[u]);
+  }
+  float4* pw = reinterpret_cast<float4*>(&psum[r][c * 8]);
+  pw[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  pw[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 8; ++e) qs[e] = 0.f;
+#pragma unroll
+  for (int i = 0; i < RPP; ++i) {
+    const float4* pr = reinterpret_cast<const float4*>(&psum[i][c * 8]);
+    const float4 lo = pr[0], hi = pr[1];
+    qs[0] += lo.x; qs[1] += lo.y; qs[2] += lo.z; qs[3] += lo.w;
+    qs[4] += hi.x; qs[5] += hi.y; qs[6] += hi.z; qs[7] += hi.w;
+  }
+}
+
+// dot product of one 8-wide chunk, fixed fused-multiply-add order, then the sum over the CPR lanes of a block row
+template <int CPR>
+__device__ __forceinline__ float chunk_dot_reduce(const float (&qs)[8], const float4& k0, const float4& k1) {
+  float dot = qs[0] * k0.x;
+  dot = __builtin_fmaf(qs[1], k0.y, dot);
+  dot = __builtin_fmaf(qs[2], k0.z, dot);
+  dot = __builtin_fmaf(qs[3], k0.w, dot);
+  dot = __builtin_fmaf(qs[4], k1.x, dot);
+  dot = __builtin_fmaf(qs[5], k1.y, dot);
+  dot = __builtin_fmaf(qs[6], k1.z, dot);
+  dot = __builtin_fmaf(qs[7], k1.w, dot);
+#pragma unroll
+  for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+  return dot;
+}
+
+// =====================================================================================================
 // Representative keys (Sec. 5.3): kbar[h, b, :] = mean of the prompt rows of block b.  A pure HBM scan:
 // one workgroup per (block, head); every wave instruction reads 1 KB of consecutive bytes; eight
 // independent 16-byte non-temporal loads per thread are in flight before the first add.
+// WITH_REL: the same scan also emits the block's partial relevance part[h, b] = qsum^h . kbar^h_b (Eq. 7), so that
+// scoring blocks from raw K needs one launch and never writes or re-reads kbar (kbar may then be null).
 // =====================================================================================================
-template <int D>
-__global__ __launch_bounds__(256) void block_means_kernel(const uint16_t* __restrict__ K, int64_t sh, int64_t sn,
-                                                          int M, int B, int n_b, float* __restrict__ kbar) {
+template <int D, bool WITH_REL>
+__global__ __launch_bounds__(256, 8) void block_means_kernel(const uint16_t* __restrict__ K, int64_t sh, int64_t sn,
+                                                          int M, int B, int n_b, float* __restrict__ kbar,
+                                                          const uint16_t* __restrict__ Q, int64_t qsh, int64_t qsn,
+                                                          const int32_t* __restrict__ focus_idx,
+                                                          const int32_t* __restrict__ counts, int n_focus_max, int n_gen,
+                                                          float* __restrict__ part) {
   constexpr int TPR = D / 8;      // threads per row (16 bytes each)
   constexpr int RPP = 256 / TPR;  // rows per pass of the workgroup
   constexpr int UNROLL = 8;
-  __shared__ float red[RPP][D];
+  __shared__ __attribute__((aligned(16))) float red[RPP][D];
+  __shared__ __attribute__((aligned(16))) float kb_sh[WITH_REL ? D : 4];
   const int b = blockIdx.x, h = blockIdx.y;
   const int r0 = b * B;
   const int len = min(B, M - r0);
   const int c = threadIdx.x % TPR, rr = threadIdx.x / TPR;
+  // the focus row this thread will need at the very end is fetched now, in the shadow of the K loads
+  int first_row = -1, n_f = 0;
+  if (WITH_REL) {
+    if (rr < n_focus_max) first_row = focus_idx[rr];
+    n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
+  }
   const uint16_t* base = K + (int64_t)h * sh + (int64_t)r0 * sn + c * 8;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int r = rr; r < len; r += RPP * UNROLL) {
@@ -148,7 +222,19 @@ __global__ __launch_bounds__(256) void block_means_kernel(const uint16_t* __rest
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < RPP; ++i) s += red[i][threadIdx.x];
-    kbar[((int64_t)h * n_b + b) * D + threadIdx.x] = s / (float)len;
+    const float mean = s / (float)len;
+    if (kbar) kbar[((int64_t)h * n_b + b) * D + threadIdx.x] = mean;
+    if (WITH_REL) kb_sh[threadIdx.x] = mean;
+  }
+  if (WITH_REL) {
+    __syncthreads();  // `red` is free again, kb_sh is complete
+    float qs[8];
+    focus_row_sum<D>(qs, Q + (int64_t)h * qsh, qsn, focus_idx, first_row, n_f, n_gen, red);
+    if (threadIdx.x < kWave) {  // the first TPR lanes carry the block row; the rest of the wave only feeds the shuffles
+      const float4* kp = reinterpret_cast<const float4*>(kb_sh + c * 8);
+      const float dot = chunk_dot_reduce<TPR>(qs, kp[0], kp[1]);
+      if (threadIdx.x == 0) part[(int64_t)h * n_b + b] = dot;
+    }
   }
 }
 
@@ -157,11 +243,27 @@ hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, 
   dim3 grid(n_b, s.n_heads);
   const uint16_t* k = static_cast<const uint16_t*>(K);
   if (s.head_dim == 128)
-    hipLaunchKernelGGL(block_means_kernel<128>, grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx, s.block,
-                       n_b, kbar);
+    hipLaunchKernelGGL((block_means_kernel<128, false>), grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx,
+                       s.block, n_b, kbar, nullptr, 0, 0, nullptr, nullptr, 0, 0, nullptr);
   else
-    hipLaunchKernelGGL(block_means_kernel<64>, grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx, s.block,
-                       n_b, kbar);
+    hipLaunchKernelGGL((block_means_kernel<64, false>), grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx,
+                       s.block, n_b, kbar, nullptr, 0, 0, nullptr, nullptr, 0, 0, nullptr);
+  return hipGetLastError();
+}
+
+// block means and partial relevances in one scan of K (kbar may be null: the means are then not stored)
+hipError_t launch_block_means_relevance(const void* K, const void* Q, const int32_t* focus_idx, const int32_t* counts,
+                                        int n_focus_max, const focus_shape& s, float* kbar, float* part, hipStream_t st) {
+  const int n_b = ceil_div(s.n_ctx, s.block);
+  dim3 grid(n_b, s.n_heads);
+  const uint16_t* k = static_cast<const uint16_t*>(K);
+  const uint16_t* q = static_cast<const uint16_t*>(Q);
+  if (s.head_dim == 128)
+    hipLaunchKernelGGL((block_means_kernel<128, true>), grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx,
+                       s.block, n_b, kbar, q, s.q_stride_h, s.q_stride_n, focus_idx, counts, n_focus_max, s.n_gen, part);
+  else
+    hipLaunchKernelGGL((block_means_kernel<64, true>), grid, dim3(256), 0, st, k, s.k_stride_h, s.k_stride_n, s.n_ctx,
+                       s.block, n_b, kbar, q, s.q_stride_h, s.q_stride_n, focus_idx, counts, n_focus_max, s.n_gen, part);
   return hipGetLastError();
 }
 
@@ -169,9 +271,8 @@ hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, 
 // Block relevance (Eq. 7), per-head partial sums: part[h, b] = qsum^h . kbar^h_b with qsum^h the SUM of the
 // focus queries of head h; the 1/(|I_focus| H) factor and the sum over heads are applied, in a fixed order,
 // by reduce_topk_kernel.  One workgroup per (group of blocks, head): a thread owns one 8-wide slice of d of
-// one block row.  The kbar loads are issued first, the focus indices are fetched speculatively (all
-// n_focus_max slots, masked by the device-side count afterwards) and the Q rows are loaded eight at a time,
-// so the whole kernel is three dependent memory round trips long.
+// one block row.  The focus indices and the kbar loads are issued first, then the focus rows of Q (see
+// focus_row_sum), so the whole kernel is two dependent memory round trips long.
 // =====================================================================================================
 template <int D>
 __global__ __launch_bounds__(256) void relevance_partial_kernel(const uint16_t* __restrict__ Q, int64_t qsh, int64_t qsn,
@@ -182,9 +283,11 @@ __global__ __launch_bounds__(256) void relevance_partial_kernel(const uint16_t* 
   constexpr int CPR = D / 8;      // lanes per block row
   constexpr int RPP = 256 / CPR;  // block rows per pass
   constexpr int PASSES = 2;
-  __shared__ int rows_sh[256];
+  __shared__ __attribute__((aligned(16))) float psum[RPP][D];
   const int t = threadIdx.x, c = t % CPR, r = t / CPR;
   const int h = blockIdx.y, b0 = blockIdx.x * (RPP * PASSES);
+  const int first_row = r < n_focus_max ? focus_idx[r] : -1;
+  const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
   float4 k0[PASSES], k1[PASSES];
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) {
@@ -197,33 +300,11 @@ __global__ __launch_bounds__(256) void relevance_partial_kernel(const uint16_t* 
       k0[p] = k1[p] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
-  int my_row = t < n_focus_max ? focus_idx[t] : -1;  // speculative: valid only below the device-side count
-  const int n_f = counts ? min(max(counts[0], 0), n_focus_max) : n_focus_max;
-  float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const uint16_t* qb = Q + (int64_t)h * qsh + c * 8;
-  for (int f0 = 0; f0 < n_f; f0 += 256) {
-    if (f0 > 0) my_row = f0 + t < n_focus_max ? focus_idx[f0 + t] : -1;
-    __syncthreads();
-    rows_sh[t] = (f0 + t < n_f && my_row >= 0 && my_row < n_gen) ? my_row : -1;
-    __syncthreads();
-    const int cnt = min(256, n_f - f0);
-    for (int f = 0; f < cnt; f += 8) {
-      uint4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int row = f + u < cnt ? rows_sh[f + u] : -1;
-        v[u] = row >= 0 ? *reinterpret_cast<const uint4*>(qb + (int64_t)row * qsn) : make_uint4(0u, 0u, 0u, 0u);
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) add_bf16x8(qs, v[u]);
-    }
-  }
+  float qs[8];
+  focus_row_sum<D>(qs, Q + (int64_t)h * qsh, qsn, focus_idx, first_row, n_f, n_gen, psum);
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) {
-    float dot = qs[0] * k0[p].x + qs[1] * k0[p].y + qs[2] * k0[p].z + qs[3] * k0[p].w + qs[4] * k1[p].x +
-                qs[5] * k1[p].y + qs[6] * k1[p].z + qs[7] * k1[p].w;
-#pragma unroll
-    for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+    const float dot = chunk_dot_reduce<CPR>(qs, k0[p], k1[p]);
     const int b = b0 + p * RPP + r;
     if (c == 0 && b < n_b) part[(int64_t)h * n_b + b] = dot;
   }

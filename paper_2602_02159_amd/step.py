@@ -41,6 +41,7 @@ class FocusStep:
             "scores": torch.empty(self.n_b, dtype=torch.float32, device=dev),
             "out": torch.zeros((self.H, self.max_active, self.d), dtype=torch.bfloat16, device=dev),
             "kbar": torch.empty((self.H, self.n_b, self.d), dtype=torch.float32, device=dev),
+            "partials": torch.empty((self.H, self.n_b), dtype=torch.float32, device=dev),
         } for _ in self.layers]
         self._keep = []  # shapes and workspaces referenced by raw pointers below
         L = fb.lib()
@@ -61,7 +62,7 @@ class FocusStep:
                                                  C.byref(s_probe), n_sink, p(self.col_mass), p(self.sink_idx), p(ws_sinks),
                                                  ws_sinks.numel()))],
             "block_means": [], "block_scores": [], "block_scores_cached": [], "sparse_attn": [], "dense_attn": [],
-            "sparse_layer": [], "sparse_layer_cached": [],
+            "sparse_layer": [], "sparse_layer_cached": [], "block_partials": [],
         }
         ws_scores = ws_attn = ws_dense = ws_layer = None
         for (q, k, v), b in zip(self.layers, self.bufs):
@@ -74,6 +75,8 @@ class FocusStep:
                 ws_dense = workspace(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, self.max_active, self.n_b, 0))
                 ws_layer = workspace(fb.workspace_bytes(fb.FN_SPARSE_LAYER, s, self.max_active, n_keep, n_sink))
             self.calls["block_means"].append((L.focus_block_means, (p(k), sp, p(b["kbar"]))))
+            self.calls["block_partials"].append((L.focus_block_partials, (
+                p(q), p(self.focus_idx), p(self.counts), k_focus, p(k), None, sp, p(b["partials"]))))
             self.calls["block_scores"].append((L.focus_block_scores, (
                 p(q), p(self.focus_idx), p(self.counts), k_focus, p(k), None, sp, n_keep, p(b["scores"]), p(b["kept"]),
                 p(ws_scores), ws_scores.numel())))

@@ -8,6 +8,7 @@ import torch
 
 import focus_inputs as fi
 from oracle import focus_oracle as fo
+from paper_2602_02159_amd import binding as fb
 
 pytestmark = pytest.mark.gpu
 
@@ -99,6 +100,39 @@ def test_block_scores_and_top_c(G):
     # counts = NULL: every slot of focus_idx is used
     scores3, _ = G.gpu_block_scores(q, G.i32(focus), None, k, None, M, B, 3)
     assert np.allclose(scores3.cpu().numpy(), Rref, atol=1e-5)
+
+
+@pytest.mark.parametrize("H,M,N,d,B,n_gen", [(8, 2000, 24, 128, 64, 48), (5, 1111, 0, 64, 128, 300), (3, 640, 8, 64, 32, 16)])
+def test_block_partials_then_top_blocks(G, H, M, N, d, B, n_gen):
+    """The two halves of block scoring: per-head partials match the oracle's per-head term of Eq. 7, the K-scanning and
+    cached-means variants agree bit for bit, and ranking the partials reproduces focus_block_scores exactly."""
+    q, k = _rand_bf16(31, H, n_gen, d).to(G.DEV), _rand_bf16(32, H, M + N, d).to(G.DEV)
+    rng = np.random.default_rng(33)
+    focus = sorted(rng.choice(n_gen, size=min(n_gen, 11), replace=False).tolist())
+    if n_gen == 300:
+        focus = sorted(rng.choice(n_gen, size=280, replace=False).tolist())   # more focus rows than one pass of the workgroup holds
+    n_b = -(-M // B)
+    fidx, counts = G.i32(focus + [-1, -1]), G.i32([len(focus), 0])
+    s = fb.make_shape(q, k, None, M, B)
+    part = torch.full((H, n_b), float("nan"), dtype=torch.float32, device=G.DEV)
+    fb.block_partials(q, fidx, counts, k, None, s, part)
+    kbar = G.gpu_block_means(k, M, B)
+    part2 = torch.full_like(part, float("nan"))
+    fb.block_partials(q, fidx, counts, None, kbar, s, part2)
+    torch.cuda.synchronize()
+    assert torch.equal(part, part2)
+    kb_ref = fo.block_means(G.to_np(k), M, B)
+    qsum = G.to_np(q).astype(np.float64)[:, focus].sum(axis=1)                       # [H, d]
+    ref = np.einsum("hbd,hd->hb", kb_ref, qsum)
+    assert np.allclose(part.cpu().numpy(), ref, rtol=0, atol=1e-4)
+    for n_keep in (0, 3, n_b):
+        scores = torch.full((n_b,), float("nan"), dtype=torch.float32, device=G.DEV)
+        kept = G.i32(None, max(n_keep, 1))
+        fb.top_blocks(part, counts, fidx.numel(), n_keep, scores, kept)
+        scores_b, kept_b = G.gpu_block_scores(q, fidx, counts, k, None, M, B, n_keep)
+        assert torch.equal(scores, scores_b) and torch.equal(kept[:n_keep], kept_b)
+        Rref = fo.block_relevance(G.to_np(q), focus, kb_ref)
+        assert np.allclose(scores.cpu().numpy(), Rref, atol=1e-5)
 
 
 def test_top_c_ties_go_to_the_lower_block(G):

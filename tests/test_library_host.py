@@ -47,7 +47,7 @@ def test_host_helpers(L):
 
 def test_workspace_sizes(L):
     s = _shape()
-    assert fb.workspace_bytes(fb.FN_BLOCK_SCORES, s) >= 4 * 16 * 64 * 4 + 16 * 4
+    assert fb.workspace_bytes(fb.FN_BLOCK_SCORES, s) >= 4 * 16 * 4 + 16 * 4     # per-head partials + scores
     assert fb.workspace_bytes(fb.FN_FIND_SINKS, s, 8) >= 4 * 1056 * 16 * 4
     assert fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, 8, 4, 2) > 0
     assert fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, 8, 17, 2) == 0      # n_keep > n_b
@@ -79,6 +79,14 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.focus_block_scores(fake, fake, None, 8, None, None, sp, 4, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_block_scores(fake, fake, None, 8, fake, None, sp, 4, None, fake, None, 0, None) == fb.FOCUS_EWORKSPACE
     assert L.focus_block_scores(fake, fake, None, 8, fake, None, sp, 4, None, fake, fake, 16, None) == fb.FOCUS_EWORKSPACE
+    # the two halves of block scores: NULL output, neither kbar nor K, too many focus slots; bad part / keep counts
+    assert L.focus_block_partials(fake, fake, None, 8, fake, None, sp, None, None) == fb.FOCUS_EINVAL
+    assert L.focus_block_partials(fake, fake, None, 8, None, None, sp, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_block_partials(fake, fake, None, 33, fake, None, sp, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_top_blocks(fake, 0, None, 8, 16, 4, fake, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_top_blocks(fake, 4, None, 8, 16, 17, fake, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, None, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, fake, None, None) == fb.FOCUS_EINVAL
     # find sinks: n_sink out of range, workspace too small
     assert L.focus_find_sinks(fake, fake, None, 8, fake, sp, 2000, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_find_sinks(fake, fake, None, 8, fake, sp, 2, None, fake, fake, 1024, None) == fb.FOCUS_EWORKSPACE
