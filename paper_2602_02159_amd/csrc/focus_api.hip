@@ -98,7 +98,7 @@ static ScoreWs ws_block_scores(const focus_shape& s) {
 }
 
 struct SinkWs {
-  size_t logits, part_ml, lse2, col_mass, total;
+  size_t logits, part_ml, lse2, col_mass, cand, total;
 };
 static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
   SinkWs w;
@@ -111,6 +111,8 @@ static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
   off += align_up((size_t)s.n_heads * p.q_pad * sizeof(float));
   w.col_mass = off;
   off += align_up(L * sizeof(float));
+  w.cand = off;  // first-round nominees of the sink tournament
+  off += align_up((size_t)kTournamentMaxCand * sizeof(int32_t));
   w.total = off;
   return w;
 }
@@ -289,9 +291,15 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   if (e != hipSuccess) return launch_fail("focus_find_sinks(logits)", e);
   e = launch_lse_combine(part_ml, shape->n_heads, p.q_pad, p.n_split, lse2, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(lse)", e);
-  e = launch_column_mass(logits, lse2, counts, max_active, shape->n_heads, L, p.q_pad, S, st);
+  // few sinks: the column-mass groups nominate, one small workgroup decides; many sinks: radix select over all of S
+  const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
+  int32_t* cand = tournament ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  e = launch_column_mass(logits, lse2, counts, max_active, shape->n_heads, L, p.q_pad, S, shape->n_ctx, n_sink, cand, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
-  if (n_sink > 0) {
+  if (tournament) {
+    e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N, tournament)", e);
+  } else if (n_sink > 0) {
     e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N)", e);
   }

@@ -359,11 +359,17 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
 
 // logits: [H, L, q_pad] fp32.  Workgroup = 64 keys x 4 head groups; thread (key, hg) walks heads hg, hg+4, ...
 // QP16 = true: q_pad == 16, the loads of four heads (16 x 16 bytes) are issued before the first exp2.
+// With cand != nullptr (small N_sink) the workgroup also plays the first round of the sink tournament: the n_sink
+// largest masses among its own prompt positions (j < M; ties to the lower j) go to cand[wg * n_sink ..], ascending,
+// padded with -1.  The overall Top-N_sink is a subset of the union of these lists (sink_final_kernel).
 template <bool QP16>
 __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restrict__ logits, const float* __restrict__ lse2,
                                                           const int32_t* __restrict__ counts, int max_active, int H, int L,
-                                                          int q_pad, float* __restrict__ col_mass) {
+                                                          int q_pad, float* __restrict__ col_mass, int M, int n_sink,
+                                                          int32_t* __restrict__ cand) {
   __shared__ float red[4][64];
+  __shared__ __attribute__((aligned(16))) uint32_t ckeys[256];
+  __shared__ uint32_t ctotal;
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
   const int kj = threadIdx.x & 63, hg = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + kj;
@@ -417,20 +423,77 @@ __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restric
   }
   red[hg][kj] = acc;
   __syncthreads();
+  float mass = 0.f;
   if (hg == 0 && j < L) {
     const float tot = (red[0][kj] + red[1][kj]) + (red[2][kj] + red[3][kj]);
-    col_mass[j] = n_act > 0 ? tot / ((float)H * (float)n_act) : 0.f;
+    mass = n_act > 0 ? tot / ((float)H * (float)n_act) : 0.f;
+    col_mass[j] = mass;
+  }
+  if (cand != nullptr && blockIdx.x * 64 < M) {  // uniform over the workgroup
+    ckeys[threadIdx.x] = (hg == 0 && j < M) ? order_key(mass) + 1u : 0u;
+    __syncthreads();
+    if (hg == 0) wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * 64);
   }
 }
 
+// Final rounds of the sink tournament over the n_cand = n_groups * n_sink first-round winners (n_sink <= 16,
+// n_cand <= 4096; cand ascending in j apart from -1 padding).  Round two: wavefront w ranks candidates
+// [256 w, 256 w + 256); round three: one wavefront ranks the <= 256 survivors.  Every round keeps the order
+// (value descending, index ascending) and lists its winners by ascending position, so the result is the exact Top-N_sink
+// in ascending order.
+__global__ __launch_bounds__(1024) void sink_final_kernel(const float* __restrict__ col_mass, const int32_t* __restrict__ cand,
+                                                         int n_cand, int n_sink, int32_t* __restrict__ sink_idx) {
+  __shared__ __attribute__((aligned(16))) uint32_t keys1[16][256];
+  __shared__ __attribute__((aligned(16))) uint32_t keys2[256];
+  __shared__ int32_t win1[16][16];
+  __shared__ int32_t win2[16];
+  __shared__ uint32_t tot1[16], tot2;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  int32_t cj[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int ci = w * 256 + lane * 4 + r;
+    cj[r] = ci < n_cand ? cand[ci] : -1;
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) keys1[w][lane * 4 + r] = cj[r] >= 0 ? order_key(col_mass[cj[r]]) + 1u : 0u;
+  __syncthreads();
+  if (w * 256 < n_cand) wave_topk<4>(keys1[w], 256, n_sink, win1[w], nullptr, &tot1[w]);
+  __syncthreads();
+  if (tid < 256) {
+    const int ww = tid >> 4, i = tid & 15;
+    const int32_t slot = (ww * 256 < n_cand && i < n_sink) ? win1[ww][i] : -1;
+    keys2[tid] = slot >= 0 ? keys1[ww][slot] : 0u;
+  }
+  __syncthreads();
+  if (w == 0) wave_topk<4>(keys2, 256, n_sink, win2, nullptr, &tot2);
+  __syncthreads();
+  if (tid < n_sink) {
+    const int32_t t = win2[tid];
+    sink_idx[tid] = t >= 0 ? cand[(t >> 4) * 256 + win1[t >> 4][t & 15]] : -1;
+  }
+}
+
+bool sink_tournament_fits(int M, int n_sink) {
+  return n_sink >= 1 && n_sink <= kTournamentMaxSinks && (int64_t)ceil_div(M, 64) * n_sink <= kTournamentMaxCand;
+}
+
 hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active, int H,
-                              int L, int q_pad, float* col_mass, hipStream_t st) {
+                              int L, int q_pad, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st) {
+  if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
   if (q_pad == 16)
     hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active, H,
-                       L, q_pad, col_mass);
+                       L, q_pad, col_mass, M, n_sink, cand);
   else
     hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active,
-                       H, L, q_pad, col_mass);
+                       H, L, q_pad, col_mass, M, n_sink, cand);
+  return hipGetLastError();
+}
+
+hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
+                             hipStream_t st) {
+  if (!sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sink_final_kernel, dim3(1), dim3(1024), 0, st, col_mass, cand, ceil_div(M, 64) * n_sink, n_sink, sink_idx);
   return hipGetLastError();
 }
 

@@ -73,9 +73,11 @@ struct TopkShared {
 // lane l holds keys[l * KPL .. l * KPL + KPL).  A bitwise search finds T, the k-th largest key (32 steps of KPL
 // compares and ballot popcounts); everything above T is selected, and of the keys equal to T the ones with the
 // lowest indices until k are reached.  Output positions come from ballot prefix counts, so `out` is ascending.
-// Writes out[0..k) (tail -1), flags[0..n) if not null, and *total.  Must be called by all 64 lanes of one wavefront.
+// Writes out[0..k) = base + index (tail -1), flags[0..n) if not null, and *total.  Must be called by all 64 lanes of one
+// wavefront.
 template <int KPL>
-__device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, int32_t* out, uint8_t* flags, uint32_t* total) {
+__device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, int32_t* out, uint8_t* flags, uint32_t* total,
+                                          int base = 0) {
   const int lane = threadIdx.x & 63;
   uint32_t kv[KPL];
 #pragma unroll
@@ -121,7 +123,7 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
     const int idx = lane * KPL + r;
-    if (sel[r]) out[pos++] = idx;
+    if (sel[r]) out[pos++] = base + idx;
     if (flags && idx < n) flags[idx] = (uint8_t)sel[r];
   }
   for (int i = (int)k_eff + lane; i < k; i += kWave) out[i] = -1;

@@ -167,6 +167,7 @@ def test_find_sinks(G, H, M, N, d, n_gen, n_act, n_sink):
     margin = fo.decision_margin(Sref, n_sink, np.arange(M + N) < M)
     assert margin > 1e-5, "test inputs produce a near-tie; pick another seed"
     assert sinks.cpu().tolist() == fo.select_sinks(Sref, M, n_sink).tolist()
+    assert sinks.cpu().tolist() == fo.select_sinks(S, M, n_sink).tolist()     # the selection itself, on the device's own values
     # counts = NULL with an exact-size list gives the same answer
     col2, sinks2 = G.gpu_find_sinks(q, G.i32(list(act)), None, k, M, 64, n_sink)
     assert torch.equal(sinks, sinks2) and np.allclose(col2.cpu().numpy(), S, rtol=1e-6)
@@ -178,8 +179,26 @@ def test_find_sinks_equal_keys_fall_back_to_lowest_positions(G):
     q = _rand_bf16(10, H, 16, d).to(G.DEV)
     col, sinks = G.gpu_find_sinks(q, G.i32([0, 3, 8]), None, k, M, 64, 5)
     assert np.allclose(col.cpu().numpy(), 1.0 / (M + N), rtol=1e-5)
-    # all column masses are equal only up to rounding on the device, so check the tie rule on exact values instead
+    # all column masses are equal only up to rounding on the device, so check the tie rule on the device's own values
     assert len(set(sinks.cpu().tolist())) == 5
+    assert sinks.cpu().tolist() == fo.select_sinks(col.cpu().numpy().astype(np.float64), M, 5).tolist()
+
+
+@pytest.mark.parametrize("M,N,n_sink", [(16384, 64, 16), (16448, 0, 16), (4100, 30, 1), (4100, 30, 17), (9000, 8, 7)])
+def test_find_sinks_selection_is_exact_with_many_exact_ties(G, M, N, n_sink):
+    """Keys repeat with period 37, so column masses tie exactly across the whole prompt (and across the groups of the
+    tournament that serves small N_sink, at and just past its size limits): the sinks must be the oracle's selection
+    applied to the device's own masses, ties to the lower position."""
+    H, d, n_gen = 2, 64, 16
+    base = _rand_bf16(40, H, 37, d)
+    k = base[:, torch.arange(M + N) % 37].contiguous().to(G.DEV)
+    q = _rand_bf16(41, H, n_gen, d).to(G.DEV)
+    col, sinks = G.gpu_find_sinks(q, G.i32([1, 4, 9, 15]), None, k, M, 64, n_sink)
+    S = col.cpu().numpy().astype(np.float64)
+    assert len(np.unique(S)) <= 37 * 4                      # ties really are exact (a few rounding classes at most)
+    assert sinks.cpu().tolist() == fo.select_sinks(S, M, n_sink).tolist()
+    Sref = fo.sink_scores(G.to_np(q), [1, 4, 9, 15], G.to_np(k))
+    assert np.allclose(S, Sref, rtol=2e-4, atol=1e-9)
 
 
 # ------------------------------------------------------------------------------------------------ stage 3
