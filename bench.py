@@ -73,6 +73,48 @@ def parse_pmc(fetch_db: str, write_db: str, workload: str) -> int:
     return 0
 
 
+def parse_mfma(db: str, workload: str) -> int:
+    """MFMA utilisation per kernel from one `rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16
+    SQ_BUSY_CYCLES GRBM_GUI_ACTIVE` run of `bench.py --mode pmc`.  Prints a markdown table:
+    util = MFMA-busy cycles / (GPU-active cycles x 4 SIMDs x 256 CUs); flops = MOPS x 512; the last column prices the
+    same flops against the dense bf16 peak over the GPU-active time at 2.4 GHz."""
+    import sqlite3
+    c = sqlite3.connect(db)
+    cols = [d[0] for d in c.execute("select * from counters_collection limit 1").description]
+    disp = "dispatch_id" if "dispatch_id" in cols else ("correlation_id" if "correlation_id" in cols else None)
+    if disp is None:
+        print("no dispatch column in counters_collection; columns:", cols)
+        return 1
+    # rocprofv3 returns one value per (dispatch, counter), already summed over the hardware instances: event counts
+    # are then totals, while the cycle counter GRBM_GUI_ACTIVE is the sum over the chip's 8 XCDs (its reading for a
+    # kernel of known duration confirms this: 8 x duration x clock) and is divided by 8 to get GPU-active cycles
+    rows = c.execute(f"select {disp}, kernel_name, counter_name, sum(value) from counters_collection "
+                     f"group by {disp}, kernel_name, counter_name").fetchall()
+    per = {}
+    for d, name, cname, v in rows:
+        if "focus::" in name:
+            per.setdefault((name, d), {})[cname] = float(v) / (8.0 if cname == "GRBM_GUI_ACTIVE" else 1.0)
+    by_kernel = {}
+    for (name, d), cs in per.items():
+        by_kernel.setdefault(name, []).append(cs)
+    print(f"workload {workload}; one row per kernel: mean over its dispatches, and the largest dispatch (by MFMA work)\n")
+    print("| kernel | dispatches | MFMA busy cycles (sum over SIMDs) | GPU active cycles | MFMA util % | bf16 MFMA flops | largest dispatch: util % / flops | flops / (active time x 2.5 PFLOP/s) % |")
+    print("|---|---|---|---|---|---|---|---|")
+    n_simd = 256 * 4
+    for name in sorted(by_kernel):
+        ds = by_kernel[name]
+        g = lambda cs, k: cs.get(k, 0.0)
+        util = lambda cs: 100.0 * g(cs, "SQ_VALU_MFMA_BUSY_CYCLES") / max(g(cs, "GRBM_GUI_ACTIVE") * n_simd, 1.0)
+        mean = lambda k: sum(g(cs, k) for cs in ds) / len(ds)
+        big = max(ds, key=lambda cs: g(cs, "SQ_INSTS_VALU_MFMA_MOPS_BF16"))
+        short = name.replace("void focus::", "").replace("focus::", "").split("(")[0]
+        print(f"| `{short}` | {len(ds)} | {mean('SQ_VALU_MFMA_BUSY_CYCLES'):.0f} | {mean('GRBM_GUI_ACTIVE'):.0f} | "
+              f"{sum(util(cs) for cs in ds) / len(ds):.2f} | {mean('SQ_INSTS_VALU_MFMA_MOPS_BF16') * 512:.3e} | "
+              f"{util(big):.2f} / {g(big, 'SQ_INSTS_VALU_MFMA_MOPS_BF16') * 512:.3e} | "
+              f"{100.0 * mean('SQ_INSTS_VALU_MFMA_MOPS_BF16') * 512 / max(mean('GRBM_GUI_ACTIVE') / 2.4e9 * MFMA_BF16_PEAK_TFLOPS * 1e12, 1.0):.2f} |")
+    return 0
+
+
 def parse_trace(db: str) -> int:
     """Per-kernel duration table from a `rocprofv3 --kernel-trace --stats` result database of a bench.py run.
     Launches are grouped by (kernel, grid) because the dense comparison runs through the same kernel as the sparse path."""
@@ -104,10 +146,13 @@ def main() -> int:
                          "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
     ap.add_argument("--parse-pmc", nargs=2, metavar=("FETCH_DB", "WRITE_DB"),
                     help="turn the two rocprofv3 --pmc result databases of a `--mode pmc` run into profiles/hbm_traffic_<workload>.json")
+    ap.add_argument("--parse-mfma", metavar="DB", help="print the MFMA utilisation table of a rocprofv3 --pmc database (see parse_mfma)")
     ap.add_argument("--parse-trace", metavar="DB", help="print the per-kernel table of a rocprofv3 --kernel-trace database")
     args = ap.parse_args()
     if args.parse_trace:
         return parse_trace(args.parse_trace)
+    if args.parse_mfma:
+        return parse_mfma(args.parse_mfma, args.workload)
     if args.parse_pmc:
         return parse_pmc(args.parse_pmc[0], args.parse_pmc[1], args.workload)
     if args.gpus != 1:

@@ -44,12 +44,12 @@ hipError_t launch_block_relevance(const void* Q, const int32_t* focus_idx, const
 hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* counts, int n_focus_max, float* values, int n,
                               int k, int32_t* out, hipStream_t st);
 hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_split, float* lse2, hipStream_t st);
-// Sink selection as a tournament (small N_sink): every 64-key group of the column-mass kernel nominates its own
+// Sink selection as a tournament (small N_sink): every 128-key group of the column-mass kernel nominates its own
 // Top-N_sink, one more workgroup ranks the nominees.  Limits of that path:
 constexpr int kTournamentMaxSinks = 16;
-constexpr int kTournamentMaxCand = 4096;  // ceil(M / 64) * n_sink
+constexpr int kTournamentMaxCand = 4096;  // ceil(M / 128) * n_sink
 bool sink_tournament_fits(int M, int n_sink);
-// cand: nullptr, or int32[ceil(M / 64) * n_sink] that receives the nominees (requires sink_tournament_fits)
+// cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits)
 hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active,
                               int H, int L, int q_pad, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st);
 hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,

@@ -413,7 +413,7 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(co
       key = order_key(r);
       return true;
     };
-    block_topk(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);
+    block_topk<kFusedMaxBlocks>(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);  // n_b <= 256 = blockDim.x
     FOCUS_STAMP(10);
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
       if (p.scores_out && tid < p.n_b) p.scores_out[tid] = r;

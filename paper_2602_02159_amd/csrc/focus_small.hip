@@ -11,18 +11,21 @@ namespace focus {
 // Past-confidence-guided indicator (Sec. 5.2): Eq. 4 top-k over the still-masked positions, then the
 // Eq. 5 window union clipped to [lo, hi).  One workgroup; everything stays in LDS.
 // =====================================================================================================
+// MAXN > 0: n_gen <= min(blockDim.x, MAXN) (the usual case, a generation block of 32..256 positions): the
+// radix-select path and the strided window pass are not compiled in.
 constexpr int kSelectMaxGen = 16384;
 
+template <int MAXN>
 __global__ __launch_bounds__(kTopkThreads) void select_queries_kernel(
     const float* __restrict__ conf, const uint8_t* __restrict__ masked, int n_gen, int k, int half, int lo, int hi,
     int32_t* __restrict__ focus_idx, int32_t* __restrict__ active_idx, int max_active, int32_t* __restrict__ counts) {
   __shared__ TopkShared sm;
-  __shared__ uint8_t flags[kSelectMaxGen];
+  __shared__ uint8_t flags[MAXN > 0 ? MAXN : kSelectMaxGen];
   auto keyfn = [=](int i, uint32_t& key) -> bool {
     key = order_key(conf[i]);
     return masked == nullptr || masked[i] != 0;
   };
-  block_topk(keyfn, n_gen, k, focus_idx, counts, flags, sm);  // ends with a barrier: flags are visible
+  block_topk<MAXN>(keyfn, n_gen, k, focus_idx, counts, flags, sm);  // ends with a barrier: flags are visible
 
   // window union: position p is active iff some focus position lies within `half` of it
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(kTopkThreads) void select_queries_kernel(
     return false;
   };
   uint32_t total;
-  if (n <= nt) {
+  if (MAXN > 0 || n <= nt) {
     const bool act = tid < n && is_active(lo + tid);
     const uint32_t pos = block_flag_scan(act, sm.wsum, &total);
     if (act) active_idx[pos] = lo + tid;
@@ -55,8 +58,15 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
                                  int hi, int32_t* focus_idx, int32_t* active_idx, int max_active, int32_t* counts,
                                  hipStream_t st) {
   const int threads = n_gen <= 64 ? 64 : (n_gen <= 256 ? 256 : kTopkThreads);
-  hipLaunchKernelGGL(select_queries_kernel, dim3(1), dim3(threads), 0, st, conf, masked, n_gen, k, window / 2, lo, hi,
-                     focus_idx, active_idx, max_active, counts);
+  if (n_gen <= 256)
+    hipLaunchKernelGGL(select_queries_kernel<256>, dim3(1), dim3(threads), 0, st, conf, masked, n_gen, k, window / 2, lo, hi,
+                       focus_idx, active_idx, max_active, counts);
+  else if (n_gen <= threads)
+    hipLaunchKernelGGL(select_queries_kernel<1024>, dim3(1), dim3(threads), 0, st, conf, masked, n_gen, k, window / 2, lo, hi,
+                       focus_idx, active_idx, max_active, counts);
+  else
+    hipLaunchKernelGGL(select_queries_kernel<0>, dim3(1), dim3(threads), 0, st, conf, masked, n_gen, k, window / 2, lo,
+                       hi, focus_idx, active_idx, max_active, counts);
   return hipGetLastError();
 }
 
@@ -66,6 +76,7 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
 // then Top-k over values[0..n).  With part == nullptr the values are read as they are.  One workgroup.
 // Used for Top-C over R_b (n_parts = H partial relevances) and Top-N_sink over S_j (n_parts = 0).
 // =====================================================================================================
+template <int MAXN>  // MAXN > 0: n <= min(blockDim.x, MAXN), no radix-select code
 __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* __restrict__ part, int n_parts,
                                                                    const int32_t* __restrict__ counts, int n_focus_max,
                                                                    float* __restrict__ values, int n, int k,
@@ -82,7 +93,7 @@ __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* 
       values[j] = acc;
       mine = acc;  // the value of element tid when n <= nt
     }
-    if (n > nt) {  // the radix path re-reads values written by other threads of the workgroup
+    if (MAXN == 0 && n > nt) {  // the radix path re-reads values written by other threads of the workgroup
       __threadfence_block();
       __syncthreads();
     }
@@ -90,12 +101,12 @@ __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* 
     mine = values[tid];
   }
   if (k <= 0) return;
-  if (n <= nt) {
+  if (MAXN > 0 || n <= nt) {
     auto keyfn = [=](int, uint32_t& key) -> bool {  // only ever asked for i == tid on this path
       key = order_key(mine);
       return true;
     };
-    block_topk(keyfn, n, k, out, nullptr, nullptr, sm);
+    block_topk<(MAXN > 0 ? MAXN : kTopkThreads)>(keyfn, n, k, out, nullptr, nullptr, sm);
   } else {
     auto keyfn = [=](int i, uint32_t& key) -> bool {
       key = order_key(values[i]);
@@ -109,7 +120,15 @@ __global__ __launch_bounds__(kTopkThreads) void reduce_topk_kernel(const float* 
 hipError_t launch_reduce_topk(const float* part, int n_parts, const int32_t* counts, int n_focus_max, float* values, int n,
                               int k, int32_t* out, hipStream_t st) {
   const int threads = n <= 64 ? 64 : (n <= 256 ? 256 : kTopkThreads);
-  hipLaunchKernelGGL(reduce_topk_kernel, dim3(1), dim3(threads), 0, st, part, n_parts, counts, n_focus_max, values, n, k, out);
+  if (n <= 256)
+    hipLaunchKernelGGL(reduce_topk_kernel<256>, dim3(1), dim3(threads), 0, st, part, n_parts, counts, n_focus_max, values, n, k,
+                       out);
+  else if (n <= threads)
+    hipLaunchKernelGGL(reduce_topk_kernel<1024>, dim3(1), dim3(threads), 0, st, part, n_parts, counts, n_focus_max, values, n,
+                       k, out);
+  else
+    hipLaunchKernelGGL(reduce_topk_kernel<0>, dim3(1), dim3(threads), 0, st, part, n_parts, counts, n_focus_max, values, n,
+                       k, out);
   return hipGetLastError();
 }
 
@@ -357,22 +376,24 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
   return hipGetLastError();
 }
 
-// logits: [H, L, q_pad] fp32.  Workgroup = 64 keys x 4 head groups; thread (key, hg) walks heads hg, hg+4, ...
-// QP16 = true: q_pad == 16, the loads of four heads (16 x 16 bytes) are issued before the first exp2.
+// logits: [H, L, q_pad] fp32.  Workgroup = 128 keys x 4 head groups (512 threads); thread (key, hg) walks heads
+// hg, hg+4, ...  QP16 = true: q_pad == 16, the loads of four heads (16 x 16 bytes) are issued before the first exp2.
 // With cand != nullptr (small N_sink) the workgroup also plays the first round of the sink tournament: the n_sink
 // largest masses among its own prompt positions (j < M; ties to the lower j) go to cand[wg * n_sink ..], ascending,
 // padded with -1.  The overall Top-N_sink is a subset of the union of these lists (sink_final_kernel).
+constexpr int kMassKeys = 128;
+
 template <bool QP16>
-__global__ __launch_bounds__(256) void column_mass_kernel(const float* __restrict__ logits, const float* __restrict__ lse2,
+__global__ __launch_bounds__(512) void column_mass_kernel(const float* __restrict__ logits, const float* __restrict__ lse2,
                                                           const int32_t* __restrict__ counts, int max_active, int H, int L,
                                                           int q_pad, float* __restrict__ col_mass, int M, int n_sink,
                                                           int32_t* __restrict__ cand) {
-  __shared__ float red[4][64];
+  __shared__ float red[4][kMassKeys];
   __shared__ __attribute__((aligned(16))) uint32_t ckeys[256];
   __shared__ uint32_t ctotal;
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  const int kj = threadIdx.x & 63, hg = threadIdx.x >> 6;
-  const int j = blockIdx.x * 64 + kj;
+  const int kj = threadIdx.x & (kMassKeys - 1), hg = threadIdx.x / kMassKeys;
+  const int j = blockIdx.x * kMassKeys + kj;
   float acc = 0.f;
   if (j < L) {
     if (QP16) {
@@ -429,10 +450,11 @@ __global__ __launch_bounds__(256) void column_mass_kernel(const float* __restric
     mass = n_act > 0 ? tot / ((float)H * (float)n_act) : 0.f;
     col_mass[j] = mass;
   }
-  if (cand != nullptr && blockIdx.x * 64 < M) {  // uniform over the workgroup
-    ckeys[threadIdx.x] = (hg == 0 && j < M) ? order_key(mass) + 1u : 0u;
+  if (cand != nullptr && blockIdx.x * kMassKeys < M) {  // uniform over the workgroup
+    if (threadIdx.x < 256) ckeys[threadIdx.x] = (hg == 0 && j < M) ? order_key(mass) + 1u : 0u;
     __syncthreads();
-    if (hg == 0) wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * 64);
+    if (threadIdx.x < kWave)
+      wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * kMassKeys);
   }
 }
 
@@ -458,7 +480,7 @@ __global__ __launch_bounds__(1024) void sink_final_kernel(const float* __restric
 #pragma unroll
   for (int r = 0; r < 4; ++r) keys1[w][lane * 4 + r] = cj[r] >= 0 ? order_key(col_mass[cj[r]]) + 1u : 0u;
   __syncthreads();
-  if (w * 256 < n_cand) wave_topk<4>(keys1[w], 256, n_sink, win1[w], nullptr, &tot1[w]);
+  if (w * 256 < n_cand) wave_topk<4>(keys1[w], 256, n_sink, win1[w], nullptr, &tot1[w]);  // blockDim covers these waves
   __syncthreads();
   if (tid < 256) {
     const int ww = tid >> 4, i = tid & 15;
@@ -475,25 +497,27 @@ __global__ __launch_bounds__(1024) void sink_final_kernel(const float* __restric
 }
 
 bool sink_tournament_fits(int M, int n_sink) {
-  return n_sink >= 1 && n_sink <= kTournamentMaxSinks && (int64_t)ceil_div(M, 64) * n_sink <= kTournamentMaxCand;
+  return n_sink >= 1 && n_sink <= kTournamentMaxSinks && (int64_t)ceil_div(M, kMassKeys) * n_sink <= kTournamentMaxCand;
 }
 
 hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active, int H,
                               int L, int q_pad, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st) {
   if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
   if (q_pad == 16)
-    hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active, H,
-                       L, q_pad, col_mass, M, n_sink, cand);
+    hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, logits, lse2, counts,
+                       max_active, H, L, q_pad, col_mass, M, n_sink, cand);
   else
-    hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, 64)), dim3(256), 0, st, logits, lse2, counts, max_active,
-                       H, L, q_pad, col_mass, M, n_sink, cand);
+    hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, logits, lse2, counts,
+                       max_active, H, L, q_pad, col_mass, M, n_sink, cand);
   return hipGetLastError();
 }
 
 hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st) {
   if (!sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(sink_final_kernel, dim3(1), dim3(1024), 0, st, col_mass, cand, ceil_div(M, 64) * n_sink, n_sink, sink_idx);
+  const int n_cand = ceil_div(M, kMassKeys) * n_sink;
+  const int threads = std::max(256, ceil_div(n_cand, 256) * 64);  // one wavefront per 256 nominees, at least the 256 of round three
+  hipLaunchKernelGGL(sink_final_kernel, dim3(1), dim3(threads), 0, st, col_mass, cand, n_cand, n_sink, sink_idx);
   return hipGetLastError();
 }
 

@@ -131,35 +131,47 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
 }
 
 // KeyFn: bool operator()(int i, uint32_t& key) const — false when i is not a candidate.
+// Top-k of n <= blockDim.x candidates (thread i supplies candidate i): the keys go to LDS, then ONE wavefront selects
+// (see wave_topk) while the others wait at the barrier.  Same contract as block_topk; kept apart so that kernels which
+// only ever see small n do not carry the radix-select code (these kernels start with a cold instruction cache, and
+// their run time is mostly instruction fetch).
+// MAXN: compile-time bound on n (256, 512 or 1024): wider single-wave selections than needed are not compiled in.
+template <int MAXN = kTopkThreads, class KeyFn>
+__device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, int k, int32_t* out, uint8_t* flags,
+                                                     TopkShared& sm) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  uint32_t mykey = 0;
+  const bool myvalid = tid < n && keyfn(tid, mykey);
+  __syncthreads();
+  sm.keys[tid] = myvalid ? mykey + 1u : 0u;  // threads past n store 0: not a candidate
+  for (int i = nt + tid; i < MAXN; i += nt) sm.keys[i] = 0u;
+  __syncthreads();
+  if (tid < kWave) {
+    if (MAXN <= 256 || n <= 256)
+      wave_topk<4>(sm.keys, n, k, out, flags, &sm.prefix);
+    else if (MAXN <= 512 || n <= 512)
+      wave_topk<8>(sm.keys, n, k, out, flags, &sm.prefix);
+    else
+      wave_topk<16>(sm.keys, n, k, out, flags, &sm.prefix);
+  }
+  __syncthreads();
+  return sm.prefix;
+}
+
 // Every thread of the workgroup must call this; blockDim.x <= kTopkThreads and a multiple of 64 (>= 256 when
 // n > blockDim.x).  `out` gets k entries, *out_count the number selected.  `flags`, if not null, is
 // workgroup-shared memory of n bytes that receives 1 for selected, 0 otherwise.
 // `dense_values`, if not null, is a 16-byte aligned float array whose element i is the value of candidate i and
 // every i < n is a candidate: the large-n path then fetches each thread's run with 16-byte loads.
-template <class KeyFn>
+// MAXN > 0: the caller guarantees n <= min(blockDim.x, MAXN); the radix path is not compiled in.
+template <int MAXN = 0, class KeyFn>
 __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int32_t* out, int32_t* out_count, uint8_t* flags,
                                            TopkShared& sm, const float* dense_values = nullptr) {
   const int tid = threadIdx.x, nt = blockDim.x;
   uint32_t total;
 
-  if (n <= nt) {
-    // ---- small n: keys go to LDS, then ONE wavefront selects (see wave_topk); the others wait at the barrier
-    uint32_t mykey = 0;
-    const bool myvalid = tid < n && keyfn(tid, mykey);
-    __syncthreads();
-    sm.keys[tid] = myvalid ? mykey + 1u : 0u;  // threads past n store 0: not a candidate
-    for (int i = nt + tid; i < kTopkThreads; i += nt) sm.keys[i] = 0u;
-    __syncthreads();
-    if (tid < kWave) {
-      if (n <= 256)
-        wave_topk<4>(sm.keys, n, k, out, flags, &sm.prefix);
-      else if (n <= 512)
-        wave_topk<8>(sm.keys, n, k, out, flags, &sm.prefix);
-      else
-        wave_topk<16>(sm.keys, n, k, out, flags, &sm.prefix);
-    }
-    __syncthreads();
-    total = sm.prefix;
+  if (MAXN > 0 || n <= nt) {
+    total = block_topk_small<(MAXN > 0 ? MAXN : kTopkThreads)>(keyfn, n, k, out, flags, sm);
   } else {
     // ---- radix select; each thread owns the contiguous run [c0, c1)
     TOPK_STAMP(0);

@@ -184,7 +184,7 @@ def test_find_sinks_equal_keys_fall_back_to_lowest_positions(G):
     assert sinks.cpu().tolist() == fo.select_sinks(col.cpu().numpy().astype(np.float64), M, 5).tolist()
 
 
-@pytest.mark.parametrize("M,N,n_sink", [(16384, 64, 16), (16448, 0, 16), (4100, 30, 1), (4100, 30, 17), (9000, 8, 7)])
+@pytest.mark.parametrize("M,N,n_sink", [(32768, 64, 16), (32800, 0, 16), (16448, 0, 16), (4100, 30, 1), (4100, 30, 17), (9000, 8, 7)])
 def test_find_sinks_selection_is_exact_with_many_exact_ties(G, M, N, n_sink):
     """Keys repeat with period 37, so column masses tie exactly across the whole prompt (and across the groups of the
     tournament that serves small N_sink, at and just past its size limits): the sinks must be the oracle's selection
