@@ -4,10 +4,12 @@
 // Order: larger value first, ties to the lower index; -0.0 == +0.0; NaN below every number.
 // Output: the selected indices in ascending order, then -1 up to k, and the count.
 //
-// Two paths, one workgroup each:
+// Three paths, one workgroup each:
+//   * n <= 256, small k : every wavefront selects among its own 64 candidates (one key per lane) by a 32-step
+//                     bitwise search over ballot popcounts, then one wavefront selects among the winners.
 //   * n <= blockDim : the keys are staged in LDS and ONE wavefront, holding up to 16 keys per lane in registers,
-//                     finds the k-th largest key by a 32-step bitwise search over ballot popcounts (no barriers,
-//                     no O(n^2) compares), then emits the selection in index order from ballot prefix counts.
+//                     finds the k-th largest key by the same bitwise search (no barriers, no O(n^2) compares),
+//                     then emits the selection in index order from ballot prefix counts.
 //   * larger n      : every thread keeps a contiguous run of up to 32 keys in registers (one pass over
 //                     memory); a radix select over the 32-bit order-preserving key (8-bit digits, LDS
 //                     histogram; digits in which all keys agree are skipped) finds the k-th key T and how many
@@ -130,20 +132,80 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
   if (lane == 0) *total = k_eff;
 }
 
+// Top-k among the 64 keys a wavefront holds one per lane (key1 = order key + 1, or 0 for "not a candidate"), same
+// order and tie rule as wave_topk.  Returns whether this lane's key is selected; pos = its rank among the selected
+// lanes (ascending lane), count = number selected.  Must be called by all 64 lanes.
+__device__ __forceinline__ bool wave_select1(uint32_t key1, int k, uint32_t& pos, uint32_t& count) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t nvalid = (uint32_t)__popcll(__ballot(key1 != 0u));
+  const uint32_t k_eff = min((uint32_t)max(k, 0), nvalid);
+  uint32_t T = 0xffffffffu;
+  if (k_eff > 0) {
+    T = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = T | (1u << bit);
+      if ((uint32_t)__popcll(__ballot(key1 >= cand)) >= k_eff) T = cand;
+    }
+  }
+  const unsigned long long below = (1ull << lane) - 1ull;
+  const unsigned long long gt = __ballot(key1 > T), eq = __ballot(key1 == T);
+  const uint32_t need = k_eff - min((uint32_t)__popcll(gt), k_eff);  // keys equal to T still to take, lowest lanes first
+  const bool sel = key1 > T || (key1 == T && (uint32_t)__popcll(eq & below) < need);
+  pos = (uint32_t)__popcll(__ballot(sel) & below);
+  count = k_eff;
+  return sel;
+}
+
 // KeyFn: bool operator()(int i, uint32_t& key) const — false when i is not a candidate.
-// Top-k of n <= blockDim.x candidates (thread i supplies candidate i): the keys go to LDS, then ONE wavefront selects
-// (see wave_topk) while the others wait at the barrier.  Same contract as block_topk; kept apart so that kernels which
-// only ever see small n do not carry the radix-select code (these kernels start with a cold instruction cache, and
-// their run time is mostly instruction fetch).
-// MAXN: compile-time bound on n (256, 512 or 1024): wider single-wave selections than needed are not compiled in.
+// Top-k of n <= blockDim.x candidates (thread i supplies candidate i).  Same contract as block_topk; kept apart so
+// that kernels which only ever see small n do not carry the radix-select code (these kernels start with a cold
+// instruction cache, and their run time is mostly instruction fetch).
+// MAXN: compile-time bound on n (256, 512 or 1024): wider selections than needed are not compiled in.
+//  - MAXN <= 256 and k * (number of wavefronts) <= 64: a two-round tournament.  Every wavefront selects the top k of
+//    its own 64 candidates (one key per lane, 32 ballot steps), the winners meet in LDS in index order and one
+//    wavefront selects the top k of those.
+//  - otherwise the keys go to LDS and ONE wavefront selects among all of them (wave_topk) while the others wait.
 template <int MAXN = kTopkThreads, class KeyFn>
 __device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, int k, int32_t* out, uint8_t* flags,
                                                      TopkShared& sm) {
   const int tid = threadIdx.x, nt = blockDim.x;
   uint32_t mykey = 0;
   const bool myvalid = tid < n && keyfn(tid, mykey);
+  const uint32_t key1 = myvalid ? mykey + 1u : 0u;  // threads past n hold 0: not a candidate
+  const int n_waves = nt >> 6;
+  if (MAXN <= 256 && n_waves <= 4 && max(k, 0) * n_waves <= kWave) {
+    uint32_t pos, cnt;
+    const bool sel = wave_select1(key1, k, pos, cnt);
+    if (n_waves == 1) {  // a single wavefront: no LDS, no barrier
+      if (sel) out[pos] = tid;
+      if (flags && tid < n) flags[tid] = (uint8_t)sel;
+      return cnt;
+    }
+    __syncthreads();  // the caller may still be reading sm from an earlier use
+    if (tid < kWave) sm.keys[tid] = 0u;
+    if (flags && tid < n) flags[tid] = 0;
+    __syncthreads();
+    if (sel) {
+      const int slot = (tid >> 6) * k + (int)pos;  // ascending slot <=> ascending candidate index
+      sm.keys[slot] = key1;
+      sm.hist[slot] = (uint32_t)tid;
+    }
+    __syncthreads();
+    if (tid < kWave) {
+      uint32_t pos2, cnt2;
+      const bool sel2 = wave_select1(sm.keys[tid], k, pos2, cnt2);
+      if (sel2) {
+        const uint32_t orig = sm.hist[tid];
+        out[pos2] = (int32_t)orig;
+        if (flags) flags[orig] = 1;
+      }
+      if (tid == 0) sm.prefix = cnt2;
+    }
+    __syncthreads();
+    return sm.prefix;
+  }
   __syncthreads();
-  sm.keys[tid] = myvalid ? mykey + 1u : 0u;  // threads past n store 0: not a candidate
+  sm.keys[tid] = key1;
   for (int i = nt + tid; i < MAXN; i += nt) sm.keys[i] = 0u;
   __syncthreads();
   if (tid < kWave) {
