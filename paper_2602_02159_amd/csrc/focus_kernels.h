@@ -22,6 +22,7 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 // per workgroup, n_split workgroups per (head, query group).
 struct SplitPlan {
   int n_sub, per_split, n_split;
+  bool pipelined = false;  // attention only: wavefronts walk several sub-tiles, use the double-buffered key loop
   int q_tiles, q_tiles_per_group, q_groups, q_pad;  // q_pad = 16 * q_tiles
 };
 

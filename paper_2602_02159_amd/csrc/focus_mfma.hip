@@ -67,6 +67,14 @@ constexpr int kStreamPolicy = 2;
 
 // s_waitcnt vmcnt(0): every outstanding global load, LDS-direct ones included, has landed
 __device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt vmcnt(N): all but the N most recently issued vector memory loads have landed (loads return in order).
+// Used by the double-buffered key loop: with the next sub-tile's N LDS-direct loads already in flight, the current
+// sub-tile is complete.  A smaller N than the number really issued since is always safe, a larger one never.
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // ---------------------------------------------------------------------------------------- sub-tiles
 // Which rows of K/V a sub-tile covers.  Wave-uniform.
@@ -371,16 +379,21 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
     lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
 }
 
-// FUSE = 0: kept_blocks comes from memory.
-// FUSE = 1 (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
+// FUSE bit 0 clear: kept_blocks comes from memory.
+// FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
 // them itself — every workgroup repeats this small computation instead of waiting for a separate Top-C kernel.
-// In both cases a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
+// FUSE bit 1 set: double-buffered key loop for launches in which a wavefront walks several sub-tiles (dense
+// comparison, window-expanded queries, alpha = 0.5): the next sub-tile's rows stream into a second LDS stage while the
+// current one is multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
+// In every case a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
 // behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
 template <int D, int NQT, int FUSE>
-__global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
+__global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
   using G = Geo<D>;
   constexpr bool FUSED = (FUSE & 1) != 0;        // Top-C in the prologue
-  constexpr int kWaveLds = 2 * G::kStageBytes;  // K stage + V stage, reused for the final merge
+  constexpr bool PIPE = (FUSE & 2) != 0;         // two K/V stages per wavefront
+  constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage
+  constexpr int kWaveLds = (PIPE ? 2 : 1) * kBufBytes;  // reused for the final merge
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * kWaveLds];
 
   const int lane = threadIdx.x & 63;
@@ -460,43 +473,79 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void sparse_attn_kernel(co
   }
 
   bool first = true;
-  while (st < st_end) {
-    const uint32_t vmask = t.vmask;
-    if (vmask != 0u) {
-      wait_loads();
-      FOCUS_STAMP(3);
-      floatx4 acc[NQT][2];
-      qk_subtile<D, NQT>(acc, stageK, q, lane);
-      FOCUS_STAMP(4);
-      bf16x8 pb[NQT];
+  auto consume = [&](const char* sK, const char* sV, uint32_t vmask) {  // one staged sub-tile into the running softmax
+    FOCUS_STAMP(3);
+    floatx4 acc[NQT][2];
+    qk_subtile<D, NQT>(acc, sK, q, lane);
+    FOCUS_STAMP(4);
+    bf16x8 pb[NQT];
 #pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) {
-        float ps[8];
-        const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
-        if (!first) {
+    for (int qt = 0; qt < NQT; ++qt) {
+      float ps[8];
+      const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
+      // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
+      if (!first && __ballot(alpha != 1.f) != 0ull) {
 #pragma unroll
-          for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
-        }
-        pb[qt] = pack_bf16x8(ps);
+        for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
       }
-      FOCUS_STAMP(5);
-      // O^T[dcol][query] += V^T . P^T
-#pragma unroll
-      for (int ct = 0; ct < G::kColTiles; ++ct) {
-        const bf16x8 a = read_v_operand<D>(stageV, ct, lane);
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
-      }
-      first = false;
-      FOCUS_STAMP(6);
+      pb[qt] = pack_bf16x8(ps);
     }
-    st += kWavesPerGroup;
-    if (st < st_end) {
-      t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
-      if (t.vmask != 0u) {
-        issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-        issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+    FOCUS_STAMP(5);
+    // O^T[dcol][query] += V^T . P^T
+#pragma unroll
+    for (int ct = 0; ct < G::kColTiles; ++ct) {
+      const bf16x8 a = read_v_operand<D>(sV, ct, lane);
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
+    }
+    first = false;
+    FOCUS_STAMP(6);
+  };
+  if (!PIPE) {
+    while (st < st_end) {
+      const uint32_t vmask = t.vmask;
+      if (vmask != 0u) {
+        wait_loads();
+        consume(stageK, stageV, vmask);
       }
+      st += kWavesPerGroup;
+      if (st < st_end) {
+        t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+        if (t.vmask != 0u) {
+          issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+          issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+        }
+      }
+    }
+  } else {
+    int buf = 0;  // the stage that holds (or receives) the current sub-tile
+    while (st < st_end) {
+      const int st_next = st + kWavesPerGroup;
+      SubTile tn;
+      tn.kind = 0;
+      tn.row0 = 0;
+      tn.vmask = 0u;
+      bool in_flight = false;
+      if (st_next < st_end) {
+        tn = locate_subtile(st_next, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+        if (tn.vmask != 0u) {  // the other stage was consumed in the previous iteration
+          char* nK = stageK + (buf ^ 1) * kBufBytes;
+          issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, nK, lane);
+          issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, nK + G::kStageBytes, lane);
+          in_flight = true;
+        }
+      }
+      if (t.vmask != 0u) {
+        if (in_flight)
+          wait_loads_but<2 * G::kLoads>();  // the 2 * kLoads loads just issued may still be under way
+        else
+          wait_loads();
+        const char* cK = stageK + buf * kBufBytes;
+        consume(cK, cK + G::kStageBytes, t.vmask);
+      }
+      if (in_flight) buf ^= 1;
+      t = tn;
+      st = st_next;
     }
   }
   FOCUS_STAMP(7);
@@ -586,8 +635,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
 template <int D, int NQT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  if (fused)
+  const bool pipe = p.pipelined;
+  if (fused && pipe)
+    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 3>), grid, dim3(256), 0, st, a);
+  else if (fused)
     hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 1>), grid, dim3(256), 0, st, a);
+  else if (pipe)
+    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 2>), grid, dim3(256), 0, st, a);
   else
     hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 0>), grid, dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
