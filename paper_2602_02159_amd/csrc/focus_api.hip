@@ -53,9 +53,12 @@ SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n
   plan_queries(p, max_active);
   p.n_sub = n_keep * ceil_div(s.block, kSubTile) + ceil_div(s.n_resp, kSubTile) + ceil_div(n_sink, kSubTile);
   plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS", 1024));
-  // Many sub-tiles per wavefront (dense comparison, alpha = 0.5, window-expanded queries): fewer, longer workgroups
-  // with the double-buffered key loop.  One sub-tile per wavefront (the 3 % keep configurations): nothing to overlap.
-  if (p.per_split > kWavesPerGroup && env_int("FOCUS_ATTN_PIPE", 1) == 1) {
+  // Many sub-tiles per wavefront (dense comparison, alpha = 0.5) or several query tiles per workgroup (window-expanded
+  // queries): fewer, longer workgroups with double-buffered key loops.  One sub-tile per wavefront (the 3 % keep
+  // configurations): nothing to overlap.
+  if (p.q_tiles_per_group > 1) {
+    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 1024));
+  } else if (p.per_split > kWavesPerGroup && env_int("FOCUS_ATTN_PIPE", 1) == 1) {
     plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 512));
     p.pipelined = p.per_split > kWavesPerGroup;
   }

@@ -67,14 +67,6 @@ constexpr int kStreamPolicy = 2;
 
 // s_waitcnt vmcnt(0): every outstanding global load, LDS-direct ones included, has landed
 __device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-// s_waitcnt vmcnt(N): all but the N most recently issued vector memory loads have landed (loads return in order).
-// Used by the double-buffered key loop: with the next sub-tile's N LDS-direct loads already in flight, the current
-// sub-tile is complete.  A smaller N than the number really issued since is always safe, a larger one never.
-template <int N>
-__device__ __forceinline__ void wait_loads_but() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
 
 // ---------------------------------------------------------------------------------------- sub-tiles
 // Which rows of K/V a sub-tile covers.  Wave-uniform.
@@ -172,6 +164,36 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, kStreamPolicy);
   }
+}
+
+// The same sub-tile through registers, for the double-buffered key loops: fetch_subtile requests the rows (the
+// loads stay in flight while the previous sub-tile is multiplied), store_subtile puts them into a stage in exactly
+// the layout issue_subtile produces.  (LDS-direct loads cannot be overlapped with LDS reads of another stage: the
+// compiler cannot tell the stages apart and waits for every outstanding LDS-direct load before each LDS read.)
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+template <int D>
+__device__ __forceinline__ void fetch_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
+                                              const int32_t* __restrict__ sink_idx, int n_sink, int lane,
+                                              uintx4 (&r)[Geo<D>::kLoads]) {
+  using G = Geo<D>;
+  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
+  const int last = 31 - __builtin_clz(t.vmask);
+#pragma unroll
+  for (int i = 0; i < G::kLoads; ++i) {
+    const int slot = i * G::kRowsPerLoad + sub;
+    int row = t.row0 + min(slot, last);
+    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
+      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
+      row = ((t.vmask >> slot) & 1u) ? s : 0;
+    }
+    const int chunk = pos ^ (slot & (G::kChunks - 1));
+    r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
+  }
+}
+template <int D>
+__device__ __forceinline__ void store_subtile(char* stage, int lane, const uintx4 (&r)[Geo<D>::kLoads]) {
+#pragma unroll
+  for (int i = 0; i < Geo<D>::kLoads; ++i) *reinterpret_cast<uintx4*>(stage + i * 1024 + lane * 16) = r[i];
 }
 
 // ---------------------------------------------------------------------------------------- queries
@@ -379,32 +401,49 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
     lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
 }
 
+// One workgroup = four wavefronts on one (head, key split, group of QT query tiles).
+//
+// QT = 1 (up to 16 active queries): every wavefront owns its sub-tiles end to end — it stages them, multiplies them
+//   against the one query tile and keeps its own running softmax; the four states are merged at the end.
+// QT = 2 / 4 (17..32 / 33..64 active queries per group): the staged sub-tiles are shared.  A round stages four
+//   sub-tiles (wavefront w loads slot w); wavefront w then works for query tile w % QT on the slots
+//   w / QT, w / QT + 4 / QT, ...  Every K/V byte is still fetched once per workgroup, every wavefront carries the
+//   accumulators of ONE query tile (32 registers instead of 32 QT), and with QT = 4 nothing is left to merge.
+//
 // FUSE bit 0 clear: kept_blocks comes from memory.
 // FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
 // them itself — every workgroup repeats this small computation instead of waiting for a separate Top-C kernel.
-// FUSE bit 1 set: double-buffered key loop for launches in which a wavefront walks several sub-tiles (dense
-// comparison, window-expanded queries, alpha = 0.5): the next sub-tile's rows stream into a second LDS stage while the
-// current one is multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
+// FUSE bit 1 set (QT = 1 only): double-buffered key loop for launches in which a wavefront walks several sub-tiles
+// (the dense comparison): the next sub-tile's rows stream into a second LDS stage while the current one is
+// multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
 // In every case a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
 // behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
-template <int D, int NQT, int FUSE>
-__global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
+template <int D, int QT, int FUSE>
+__global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
   using G = Geo<D>;
-  constexpr bool FUSED = (FUSE & 1) != 0;        // Top-C in the prologue
-  constexpr bool PIPE = (FUSE & 2) != 0;         // two K/V stages per wavefront
-  constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage
-  constexpr int kWaveLds = (PIPE ? 2 : 1) * kBufBytes;  // reused for the final merge
-  __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * kWaveLds];
+  constexpr bool FUSED = (FUSE & 1) != 0;                // Top-C in the prologue
+  constexpr bool SHARED = QT > 1;                        // staged sub-tiles are shared by the wavefronts
+  constexpr bool PIPE = (FUSE & 2) != 0;                 // QT = 1 only: two K/V stages per wavefront
+  static_assert(!(PIPE && SHARED), "shared sub-tiles are single-buffered");
+  constexpr int KG = kWavesPerGroup / QT;                // wavefronts per query tile, each on its own sub-tiles
+  constexpr int kBufBytes = 2 * G::kStageBytes;          // one slot: K stage + V stage of a sub-tile
+  static_assert(QT == 1 || QT == 2 || QT == 4, "query tiles per workgroup");
+  static_assert(16 * D * 4 + 16 * 2 * 4 <= kBufBytes, "merge scratch fits a wavefront's slot");
+  // Two buffers of four slots (slot w is filled by wavefront w); the second exists in the double-buffered variants.
+  __shared__ __attribute__((aligned(16))) char ldsA[kWavesPerGroup * kBufBytes];
+  __shared__ __attribute__((aligned(16))) char ldsB[PIPE ? kWavesPerGroup * kBufBytes : 16];
+  __shared__ uint32_t maskA[kWavesPerGroup];  // SHARED: the keys of each slot that take part
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, h = blockIdx.y, qg = blockIdx.z;
-  const int q_base = qg * NQT * kQTile;
+  const int qt = wave % QT, kg = wave / QT;
+  const int q0 = (qg * QT + qt) * kQTile;  // first position in the active list of this wavefront's query tile
   FOCUS_STAMP(0);
   FOCUS_STAMP(1);
 
-  char* stageK = lds + wave * kWaveLds;
+  char* stageK = ldsA + wave * kBufBytes;
   char* stageV = stageK + G::kStageBytes;
   const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
@@ -415,7 +454,7 @@ __global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void 
   __shared__ int32_t kept_sh[FUSED ? kFusedMaxBlocks : 1];
   const int32_t* kept_blocks = p.kept_blocks;
   if (FUSED) {
-    // R_b = (1 / (|I_focus| H)) sum_h part[h, b] for b = threadIdx.x (n_b <= 256), then Top-C by rank counting
+    // R_b = (1 / (|I_focus| H)) sum_h part[h, b] for b = threadIdx.x (n_b <= 256), then Top-C
     const int tid = threadIdx.x;
     float r = 0.f;
     if (tid < p.n_b) r = sum_partials(p.rel_part, p.H, p.n_b, tid);
@@ -440,68 +479,101 @@ __global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void 
   const int st_begin = split * p.per_split;
   const int st_end = min(st_begin + p.per_split, p.n_sub);
   int st = st_begin + wave;
-  int qrow[NQT];
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) qrow[qt] = fetch_q_row(p.active_idx, q_base + qt * kQTile, p.max_active, p.n_gen, lane);
+  const int qrow = fetch_q_row(p.active_idx, q0, p.max_active, p.n_gen, lane);
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
+  uintx4 rk[G::kLoads], rv[G::kLoads];  // PIPE: the sub-tile in flight
   if (st < st_end) {
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
     if (t.vmask != 0u) {
-      issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-      issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+      if (PIPE) {
+        fetch_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, lane, rk);
+        fetch_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, lane, rv);
+      } else {
+        issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+        issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+      }
     }
   }
+  if (SHARED && lane == 0) maskA[wave] = t.vmask;
   FOCUS_STAMP(2);
-  bf16x8 q[NQT][G::kKSteps];
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) load_q_tile<D>(q[qt], Qh, p.qsn, qrow[qt], lane);
+  bf16x8 q[1][G::kKSteps];
+  load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
   const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) mask_q_tile<D>(q[qt], q_base + qt * kQTile, n_act, lane);
+  mask_q_tile<D>(q[0], q0, n_act, lane);
 
-  float m_run[NQT], l_run[NQT];
-  floatx4 o[NQT][G::kColTiles];
+  float m_run = -INFINITY, l_run = 0.f;
+  floatx4 o[G::kColTiles];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    m_run[qt] = -INFINITY;
-    l_run[qt] = 0.f;
-#pragma unroll
-    for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   bool first = true;
   auto consume = [&](const char* sK, const char* sV, uint32_t vmask) {  // one staged sub-tile into the running softmax
     FOCUS_STAMP(3);
-    floatx4 acc[NQT][2];
-    qk_subtile<D, NQT>(acc, sK, q, lane);
+    floatx4 acc[1][2];
+    qk_subtile<D, 1>(acc, sK, q, lane);
     FOCUS_STAMP(4);
-    bf16x8 pb[NQT];
+    float ps[8];
+    const float alpha = softmax_step(acc[0], vmask, g, p.scale_log2, m_run, l_run, ps);
+    // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
+    if (!first && __ballot(alpha != 1.f) != 0ull) {
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      float ps[8];
-      const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
-      // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
-      if (!first && __ballot(alpha != 1.f) != 0ull) {
-#pragma unroll
-        for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
-      }
-      pb[qt] = pack_bf16x8(ps);
+      for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] *= alpha;
     }
+    const bf16x8 pb = pack_bf16x8(ps);
     FOCUS_STAMP(5);
     // O^T[dcol][query] += V^T . P^T
 #pragma unroll
     for (int ct = 0; ct < G::kColTiles; ++ct) {
       const bf16x8 a = read_v_operand<D>(sV, ct, lane);
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
+      o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, o[ct], 0, 0, 0);
     }
     first = false;
     FOCUS_STAMP(6);
   };
-  if (!PIPE) {
+  auto no_tile = []() {
+    SubTile e;
+    e.kind = 0;
+    e.row0 = 0;
+    e.vmask = 0u;
+    return e;
+  };
+  auto locate = [&](int sub) {
+    return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+  };
+  if (PIPE && t.vmask != 0u) {  // the first sub-tile: registers -> this wavefront's slot of buffer A
+    store_subtile<D>(stageK, lane, rk);
+    store_subtile<D>(stageV, lane, rv);
+  }
+  if (SHARED) {
+    // One round = four staged sub-tiles.  Single-buffered: two workgroups share a compute unit, and while one waits
+    // for its rows the other multiplies.
+    for (int base = st_begin; base < st_end; base += kWavesPerGroup) {  // uniform over the workgroup
+      wait_loads();     // this wavefront's slot of the round has landed ...
+      __syncthreads();  // ... and so has everyone's
+      uint32_t vm[QT];
+#pragma unroll
+      for (int j = 0; j < QT; ++j) vm[j] = __builtin_amdgcn_readfirstlane(maskA[kg + j * KG]);
+#pragma unroll
+      for (int j = 0; j < QT; ++j) {
+        if (vm[j] != 0u) {
+          const char* cK = ldsA + (kg + j * KG) * kBufBytes;
+          consume(cK, cK + G::kStageBytes, vm[j]);
+        }
+      }
+      __syncthreads();  // everyone is done with the slots and their masks
+      const int st_n = base + kWavesPerGroup + wave;
+      SubTile tn = no_tile();
+      if (st_n < st_end) tn = locate(st_n);
+      if (lane == 0) maskA[wave] = tn.vmask;
+      if (tn.vmask != 0u) {
+        issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, stageK, lane);
+        issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, stageV, lane);
+      }
+    }
+  } else if (!PIPE) {
     while (st < st_end) {
       const uint32_t vmask = t.vmask;
       if (vmask != 0u) {
@@ -510,7 +582,7 @@ __global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void 
       }
       st += kWavesPerGroup;
       if (st < st_end) {
-        t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+        t = locate(st);
         if (t.vmask != 0u) {
           issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
           issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
@@ -518,80 +590,77 @@ __global__ __launch_bounds__(256, ((NQT == 1 && (FUSE & 2) == 0) ? 2 : 1)) void 
       }
     }
   } else {
-    int buf = 0;  // the stage that holds (or receives) the current sub-tile
-    while (st < st_end) {
+    // One step: the sub-tile `t` sits in this wavefront's slot of `cur`; the next one is requested into registers
+    // before `t` is multiplied and stored into the slot of `nxt` afterwards.  No barrier: the slots are private.
+    auto step = [&](const char* cur, char* nxt) {
       const int st_next = st + kWavesPerGroup;
-      SubTile tn;
-      tn.kind = 0;
-      tn.row0 = 0;
-      tn.vmask = 0u;
-      bool in_flight = false;
-      if (st_next < st_end) {
-        tn = locate_subtile(st_next, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
-        if (tn.vmask != 0u) {  // the other stage was consumed in the previous iteration
-          char* nK = stageK + (buf ^ 1) * kBufBytes;
-          issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, nK, lane);
-          issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, nK + G::kStageBytes, lane);
-          in_flight = true;
-        }
+      SubTile tn = no_tile();
+      if (st_next < st_end) tn = locate(st_next);
+      if (tn.vmask != 0u) {
+        fetch_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, lane, rk);
+        fetch_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, lane, rv);
       }
-      if (t.vmask != 0u) {
-        if (in_flight)
-          wait_loads_but<2 * G::kLoads>();  // the 2 * kLoads loads just issued may still be under way
-        else
-          wait_loads();
-        const char* cK = stageK + buf * kBufBytes;
-        consume(cK, cK + G::kStageBytes, t.vmask);
+      if (t.vmask != 0u) consume(cur, cur + G::kStageBytes, t.vmask);
+      if (tn.vmask != 0u) {
+        store_subtile<D>(nxt, lane, rk);
+        store_subtile<D>(nxt + G::kStageBytes, lane, rv);
       }
-      if (in_flight) buf ^= 1;
       t = tn;
       st = st_next;
+    };
+    char* mineA = ldsA + wave * kBufBytes;
+    char* mineB = ldsB + wave * kBufBytes;
+    while (st < st_end) {
+      step(mineA, mineB);
+      if (st < st_end) step(mineB, mineA);
     }
   }
   FOCUS_STAMP(7);
 
-  // ---- merge the four wavefronts, one query tile at a time, through each wave's own LDS slice
+  // ---- merge the wavefronts that share a query tile through each wavefront's own LDS slice
   float* myO = reinterpret_cast<float*>(stageK);               // [16][D]
   float* myML = reinterpret_cast<float*>(stageK + 16 * D * 4);  // [16][2]
   constexpr int kPerThread = D / 16;                            // output columns per thread in the merge
   constexpr int kVec = kPerThread / 4;
   const int mq = threadIdx.x >> 4;                              // query of the tile this thread merges
   const int mc = (threadIdx.x & 15) * kPerThread;
+  wait_loads();
+  __syncthreads();  // every staged sub-tile has been consumed by everyone
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    __syncthreads();
+  for (int ct = 0; ct < G::kColTiles; ++ct) *reinterpret_cast<floatx4*>(myO + c * D + ct * 16 + 4 * g) = o[ct];
+  if (g == 0) *reinterpret_cast<float2*>(myML + 2 * c) = make_float2(m_run, l_run);
+  __syncthreads();
 #pragma unroll
-    for (int ct = 0; ct < G::kColTiles; ++ct)
-      *reinterpret_cast<floatx4*>(myO + c * D + ct * 16 + 4 * g) = o[qt][ct];
-    if (g == 0) *reinterpret_cast<float2*>(myML + 2 * c) = make_float2(m_run[qt], l_run[qt]);
-    __syncthreads();
-    float2 ml[kWavesPerGroup];
-    float4 ow[kWavesPerGroup][kVec];
+  for (int tq = 0; tq < QT; ++tq) {
+    float2 ml[KG];
+    float4 ow[KG][kVec];
 #pragma unroll
-    for (int w = 0; w < kWavesPerGroup; ++w) {
-      const char* wbase = lds + w * kWaveLds;
-      ml[w] = *reinterpret_cast<const float2*>(wbase + 16 * D * 4 + 8 * mq);
+    for (int k = 0; k < KG; ++k) {
+      const char* wbase = ldsA + (tq + QT * k) * kBufBytes;
+      ml[k] = *reinterpret_cast<const float2*>(wbase + 16 * D * 4 + 8 * mq);
 #pragma unroll
-      for (int i = 0; i < kVec; ++i) ow[w][i] = *reinterpret_cast<const float4*>(wbase + (mq * D + mc + 4 * i) * 4);
+      for (int i = 0; i < kVec; ++i) ow[k][i] = *reinterpret_cast<const float4*>(wbase + (mq * D + mc + 4 * i) * 4);
     }
-    float mmax = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
+    float mmax = ml[0].x;
+#pragma unroll
+    for (int k = 1; k < KG; ++k) mmax = fmaxf(mmax, ml[k].x);
     float acc_o[kPerThread];
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) acc_o[i] = 0.f;
     float lsum = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWavesPerGroup; ++w) {
-      const float f = ml[w].y > 0.f ? __builtin_amdgcn_exp2f(ml[w].x - mmax) : 0.f;
-      lsum += f * ml[w].y;
+    for (int k = 0; k < KG; ++k) {
+      const float f = ml[k].y > 0.f ? __builtin_amdgcn_exp2f(ml[k].x - mmax) : 0.f;
+      lsum += f * ml[k].y;
 #pragma unroll
       for (int i = 0; i < kVec; ++i) {
-        acc_o[4 * i] += f * ow[w][i].x;
-        acc_o[4 * i + 1] += f * ow[w][i].y;
-        acc_o[4 * i + 2] += f * ow[w][i].z;
-        acc_o[4 * i + 3] += f * ow[w][i].w;
+        acc_o[4 * i] += f * ow[k][i].x;
+        acc_o[4 * i + 1] += f * ow[k][i].y;
+        acc_o[4 * i + 2] += f * ow[k][i].z;
+        acc_o[4 * i + 3] += f * ow[k][i].w;
       }
     }
-    const int a = q_base + qt * kQTile + mq;  // position in the active list
+    const int a = (qg * QT + tq) * kQTile + mq;  // position in the active list
     if (a < n_act) {
       if (p.n_split == 1) {
         const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
@@ -632,18 +701,18 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
   merge_splits<D>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, out, osh, osn, lse, (threadIdx.x & 15) == 0);
 }
 
-template <int D, int NQT>
+template <int D, int QT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  const bool pipe = p.pipelined;
+  const bool pipe = QT == 1 && p.pipelined;  // with shared sub-tiles (QT > 1) the rounds are always double-buffered
   if (fused && pipe)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 3>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 3 : 1)>), grid, dim3(256), 0, st, a);
   else if (fused)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 1>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 1>), grid, dim3(256), 0, st, a);
   else if (pipe)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 2>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 2 : 0)>), grid, dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL((sparse_attn_kernel<D, NQT, 0>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 0>), grid, dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
