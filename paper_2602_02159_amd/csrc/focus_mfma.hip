@@ -35,11 +35,23 @@ __device__ long long* g_stamps;
 #define FOCUS_STAMP(i)                                                                                          \
   do {                                                                                                          \
     if ((threadIdx.x & 63) == 0)                                                                                \
-      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = \
+      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (i)] = \
           (i) == 0 ? wall_clock64() : clock64();                                                                \
+  } while (0)
+#define FOCUS_LAP_START(t0) long long t0 = clock64()
+// accumulates clock64() - t0 into slot i of the wavefront's stamp row and restarts t0
+#define FOCUS_LAP(i, t0)                                                                                        \
+  do {                                                                                                          \
+    const long long now_ = clock64();                                                                           \
+    if ((threadIdx.x & 63) == 0)                                                                                \
+      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (i)] += \
+          now_ - (t0);                                                                                          \
+    (t0) = now_;                                                                                                \
   } while (0)
 #else
 #define FOCUS_STAMP(i)
+#define FOCUS_LAP_START(t0)
+#define FOCUS_LAP(i, t0)
 #endif
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -81,11 +93,16 @@ __device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xfffffff
 // Locate sub-tile `st` of the attention key list: kept blocks first (n_keep * sub_per_block sub-tiles), then
 // the response rows, then the sinks.  Block ids outside [0, n_b) are skipped.  The union of Eq. 8 is a set:
 // a sink is dropped when it is outside the prompt, inside a kept block or listed earlier in sink_idx (the block
-// list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r and the two index lists are
-// scanned 64 entries per load.
+// list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r.
+//   "inside a kept block": one look-up in `kept_bits` (bit b set <=> block b is kept; LDS, built by the workgroup)
+//   when that is given, else the block list is scanned 64 entries per load.
+//   "listed earlier": a strictly ascending list (what focus_find_sinks writes) cannot repeat an entry, which a scan
+//   of 64 entries per step establishes; only other lists pay for the all-pairs comparison.
+constexpr int kBitmapBlocks = 8192;  // largest n_b for which workgroups keep a bitmap of the kept blocks
 __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
                                                   const int32_t* __restrict__ kept_blocks, int n_keep,
-                                                  const int32_t* __restrict__ sink_idx, int n_sink) {
+                                                  const int32_t* __restrict__ sink_idx, int n_sink,
+                                                  const uint32_t* kept_bits = nullptr) {
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
@@ -117,22 +134,36 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
   const bool in_prompt = mine >= 0 && mine < M;
   const int my_block = in_prompt ? mine / B : -1;
   uint32_t bad = 0u;
-  for (int j0 = 0; j0 < n_keep; j0 += kWave) {
-    const int v = j0 + lane < n_keep ? kept_blocks[j0 + lane] : -2;
+  if (kept_bits != nullptr) {
+    const bool kept = my_block >= 0 && ((kept_bits[my_block >> 5] >> (my_block & 31)) & 1u);
+    bad = (uint32_t)(__ballot(kept) & 0xffffffffull);
+  } else {
+    for (int j0 = 0; j0 < n_keep; j0 += kWave) {
+      const int v = j0 + lane < n_keep ? kept_blocks[j0 + lane] : -2;
 #pragma unroll 4
-    for (int r = 0; r < kSubTile; ++r) {
-      const int sb = __shfl(my_block, r, kWave);
-      if (__ballot(v == sb) != 0ull) bad |= 1u << r;
+      for (int r = 0; r < kSubTile; ++r) {
+        const int sb = __shfl(my_block, r, kWave);
+        if (__ballot(v == sb) != 0ull) bad |= 1u << r;
+      }
     }
   }
   const int e_end = min(t.row0 + kSubTile, n_sink);
-  for (int j0 = 0; j0 < e_end; j0 += kWave) {
+  bool ascending = true;  // sink_idx[0 .. e_end) strictly ascending?
+  for (int j0 = 0; j0 + 1 < e_end; j0 += kWave) {
     const int idx = j0 + lane;
-    const int v = idx < e_end ? sink_idx[idx] : -2;
+    const bool pair = idx + 1 < e_end;
+    const int a = pair ? sink_idx[idx] : 0, b = pair ? sink_idx[idx + 1] : 1;
+    if (__ballot(b <= a) != 0ull) ascending = false;
+  }
+  if (!ascending) {
+    for (int j0 = 0; j0 < e_end; j0 += kWave) {
+      const int idx = j0 + lane;
+      const int v = idx < e_end ? sink_idx[idx] : -2;
 #pragma unroll 4
-    for (int r = 0; r < kSubTile; ++r) {
-      const int s = __shfl(mine, r, kWave);
-      if (__ballot(v == s && idx < t.row0 + r) != 0ull) bad |= 1u << r;
+      for (int r = 0; r < kSubTile; ++r) {
+        const int s = __shfl(mine, r, kWave);
+        if (__ballot(v == s && idx < t.row0 + r) != 0ull) bad |= 1u << r;
+      }
     }
   }
   t.vmask = (uint32_t)(__ballot(in_prompt) & 0xffffffffull) & ~bad;
@@ -189,6 +220,31 @@ __device__ __forceinline__ void fetch_subtile(const uint16_t* __restrict__ base,
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
   }
+}
+// The loads [first, first + NL) of a sub-tile only (a wavefront's share when several wavefronts stage one sub-tile).
+template <int D, int NL>
+__device__ __forceinline__ void fetch_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
+                                                   const int32_t* __restrict__ sink_idx, int n_sink, int lane, int first,
+                                                   uintx4 (&r)[NL]) {
+  using G = Geo<D>;
+  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
+  const int last = 31 - __builtin_clz(t.vmask);
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int slot = (first + i) * G::kRowsPerLoad + sub;
+    int row = t.row0 + min(slot, last);
+    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
+      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
+      row = ((t.vmask >> slot) & 1u) ? s : 0;
+    }
+    const int chunk = pos ^ (slot & (G::kChunks - 1));
+    r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
+  }
+}
+template <int D, int NL>
+__device__ __forceinline__ void store_subtile_part(char* stage, int lane, int first, const uintx4 (&r)[NL]) {
+#pragma unroll
+  for (int i = 0; i < NL; ++i) *reinterpret_cast<uintx4*>(stage + (first + i) * 1024 + lane * 16) = r[i];
 }
 template <int D>
 __device__ __forceinline__ void store_subtile(char* stage, int lane, const uintx4 (&r)[Geo<D>::kLoads]) {
@@ -294,26 +350,35 @@ __device__ __forceinline__ bf16x8 read_v_operand(const char* stageV, int ct, int
 }
 
 // One step of the base-2 online softmax for the 8 logits a lane holds of one query; returns the rescale factor
-// of the running state and leaves exp2(s - m) in ps.
+// of the running state and leaves exp2(scale * s - m) in ps.  The running maximum m is kept in the scaled domain;
+// the scale (> 0) is applied to the raw maximum once and folded into the exponent's multiply-add for the rest.
+// A sub-tile whose 32 slots all hold keys (the common case) skips the per-slot masking.
 __device__ __forceinline__ float softmax_step(const floatx4 (&acc)[2], uint32_t vmask, int g, float scale_log2, float& m_run,
                                               float& l_run, float (&ps)[8]) {
   float s[8];
   float mx = -INFINITY;
+  if (vmask == 0xffffffffu) {  // wave-uniform
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-    const float v = acc[e >> 2][e & 3] * scale_log2;
-    s[e] = ((vmask >> slot) & 1u) ? v : -INFINITY;
-    mx = fmaxf(mx, s[e]);
+    for (int e = 0; e < 8; ++e) {
+      s[e] = acc[e >> 2][e & 3];
+      mx = fmaxf(mx, s[e]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
+      s[e] = ((vmask >> slot) & 1u) ? acc[e >> 2][e & 3] : -INFINITY;
+      mx = fmaxf(mx, s[e]);
+    }
   }
-  mx = group_max(mx);
+  mx = group_max(mx) * scale_log2;  // -inf stays -inf
   const float m_new = fmaxf(m_run, mx);
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
   float lsum = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    ps[e] = __builtin_amdgcn_exp2f(s[e] - m_use);
+    ps[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale_log2, -m_use));
     lsum += ps[e];
   }
   lsum = group_sum(lsum);
@@ -401,38 +466,49 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
     lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
 }
 
-// One workgroup = four wavefronts on one (head, key split, group of QT query tiles).
+// One workgroup works on one (head, key split, group of QT query tiles); the key axis is walked in rounds of four
+// 32-row sub-tiles ("slots").
 //
-// QT = 1 (up to 16 active queries): every wavefront owns its sub-tiles end to end — it stages them, multiplies them
-//   against the one query tile and keeps its own running softmax; the four states are merged at the end.
-// QT = 2 / 4 (17..32 / 33..64 active queries per group): the staged sub-tiles are shared.  A round stages four
-//   sub-tiles (wavefront w loads slot w); wavefront w then works for query tile w % QT on the slots
-//   w / QT, w / QT + 4 / QT, ...  Every K/V byte is still fetched once per workgroup, every wavefront carries the
-//   accumulators of ONE query tile (32 registers instead of 32 QT), and with QT = 4 nothing is left to merge.
+// QT = 1 (up to 16 active queries), four wavefronts: every wavefront owns its slot end to end — it stages the
+//   sub-tile, multiplies it against the one query tile and keeps its own running softmax; the four states are merged
+//   at the end.
+// QT = 2 / 4 (17..32 / 33..64 active queries per group), eight wavefronts: the staged sub-tiles are shared.
+//   Wavefronts 0..3 load the K rows of slots 0..3, wavefronts 4..7 the V rows; wavefront w then works for query tile
+//   w % QT on the slots w / QT, w / QT + 8 / QT, ...  Every K/V byte is still fetched once per workgroup, every
+//   wavefront carries the accumulators of ONE query tile, and two workgroups per compute unit put four wavefronts on
+//   each SIMD: a lone wavefront cannot hide the LDS and MFMA latencies of its own chain (measured: ~1 us per
+//   sub-tile and query tile, four times the arithmetic).
 //
 // FUSE bit 0 clear: kept_blocks comes from memory.
 // FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
 // them itself — every workgroup repeats this small computation instead of waiting for a separate Top-C kernel.
 // FUSE bit 1 set (QT = 1 only): double-buffered key loop for launches in which a wavefront walks several sub-tiles
-// (the dense comparison): the next sub-tile's rows stream into a second LDS stage while the current one is
+// (the dense comparison): the next sub-tile's rows are requested into registers while the current one is
 // multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
 // In every case a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
 // behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
 template <int D, int QT, int FUSE>
-__global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_kernel(const AttnArgs p) {
+__global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 0 ? 2 : 1))) void sparse_attn_kernel(
+    const AttnArgs p) {
   using G = Geo<D>;
   constexpr bool FUSED = (FUSE & 1) != 0;                // Top-C in the prologue
   constexpr bool SHARED = QT > 1;                        // staged sub-tiles are shared by the wavefronts
   constexpr bool PIPE = (FUSE & 2) != 0;                 // QT = 1 only: two K/V stages per wavefront
   static_assert(!(PIPE && SHARED), "shared sub-tiles are single-buffered");
-  constexpr int KG = kWavesPerGroup / QT;                // wavefronts per query tile, each on its own sub-tiles
+  constexpr int W = SHARED ? 2 * kWavesPerGroup : kWavesPerGroup;  // wavefronts in the workgroup
+  constexpr int KG = W / QT;                             // wavefronts per query tile, each on its own slots
+  constexpr int NS = kWavesPerGroup / KG;                // slots a wavefront multiplies per round (SHARED)
+  constexpr bool HALF = QT == 4;                         // SHARED in half rounds: two slots multiplied, two refilled
+  constexpr int NLH = G::kLoads / 2;                     // HALF: loads per wavefront and half round
   constexpr int kBufBytes = 2 * G::kStageBytes;          // one slot: K stage + V stage of a sub-tile
+  constexpr int kMergeBytes = 16 * D * 4;                // one wavefront's O tile in the final merge
   static_assert(QT == 1 || QT == 2 || QT == 4, "query tiles per workgroup");
-  static_assert(16 * D * 4 + 16 * 2 * 4 <= kBufBytes, "merge scratch fits a wavefront's slot");
-  // Two buffers of four slots (slot w is filled by wavefront w); the second exists in the double-buffered variants.
+  static_assert(W * kMergeBytes <= kWavesPerGroup * kBufBytes, "merge scratch fits the stages");
+  // Two buffers of four slots; the second exists in the double-buffered variant only.
   __shared__ __attribute__((aligned(16))) char ldsA[kWavesPerGroup * kBufBytes];
   __shared__ __attribute__((aligned(16))) char ldsB[PIPE ? kWavesPerGroup * kBufBytes : 16];
   __shared__ uint32_t maskA[kWavesPerGroup];  // SHARED: the keys of each slot that take part
+  __shared__ float2 ml_sh[W][16];             // final merge: running maximum and sum per wavefront and query
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -443,8 +519,10 @@ __global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_ke
   FOCUS_STAMP(0);
   FOCUS_STAMP(1);
 
-  char* stageK = ldsA + wave * kBufBytes;
+  const int slot = wave & (kWavesPerGroup - 1);  // the slot this wavefront stages
+  char* stageK = ldsA + slot * kBufBytes;
   char* stageV = stageK + G::kStageBytes;
+  const bool load_k = !SHARED || wave < kWavesPerGroup;  // SHARED: wavefronts 0..3 stage K rows, 4..7 V rows
   const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
   const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
@@ -474,30 +552,78 @@ __global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_ke
     kept_blocks = kept_sh;
   }
 
+  // Workgroups whose key range reaches the sink sub-tiles keep a bitmap of the kept blocks for the union of Eq. 8.
+  __shared__ uint32_t kept_bits_sh[kBitmapBlocks / 32];
+  const uint32_t* kept_bits = nullptr;
+  {
+    const int first_sink_sub = p.n_keep * p.sub_per_block + (p.N + kSubTile - 1) / kSubTile;
+    const int my_end = min((int)(blockIdx.x + 1) * p.per_split, p.n_sub);
+    if (p.n_sink > 0 && p.n_keep > 0 && p.n_b <= kBitmapBlocks && my_end > first_sink_sub) {  // uniform over the workgroup
+      const int words = (p.n_b + 31) >> 5;
+      for (int i = threadIdx.x; i < words; i += blockDim.x) kept_bits_sh[i] = 0u;
+      __syncthreads();
+      for (int i = threadIdx.x; i < p.n_keep; i += blockDim.x) {
+        const int b = kept_blocks[i];
+        if (b >= 0 && b < p.n_b) atomicOr(&kept_bits_sh[b >> 5], 1u << (b & 31));
+      }
+      __syncthreads();
+      kept_bits = kept_bits_sh;
+    }
+  }
+
   // Order of the memory requests: the query row ids first (tiny, they return first), then the first
   // sub-tile's K and V rows as soon as its block id is known, then the query rows and the device-side count.
   const int st_begin = split * p.per_split;
   const int st_end = min(st_begin + p.per_split, p.n_sub);
-  int st = st_begin + wave;
+  int st = st_begin + slot;
   const int qrow = fetch_q_row(p.active_idx, q0, p.max_active, p.n_gen, lane);
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
   uintx4 rk[G::kLoads], rv[G::kLoads];  // PIPE: the sub-tile in flight
-  if (st < st_end) {
-    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+  // HALF: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
+  // the half round's sub-tile (w & 1)
+  const int h_i = wave & 1, h_kv = (wave >> 1) & 1, h_first = (wave >> 2) * NLH;
+  uintx4 rh[NLH];
+  auto fetch_half = [&](int ph) {  // request this wavefront's share of half round ph; returns its sub-tile
+    SubTile tp;
+    tp.kind = 0;
+    tp.row0 = 0;
+    tp.vmask = 0u;
+    const int sub = st_begin + 2 * ph + h_i;
+    if (sub < st_end)
+      tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
+    if (tp.vmask != 0u)
+      fetch_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink, lane, h_first, rh);
+    return tp;
+  };
+  auto store_half = [&](int ph, const SubTile& tp) {  // ... and put it into its slot once the slot is free
+    const int sl = (2 * ph + h_i) & (kWavesPerGroup - 1);
+    if (tp.vmask != 0u)
+      store_subtile_part<D, NLH>(ldsA + sl * kBufBytes + h_kv * G::kStageBytes, lane, h_first, rh);
+    if (h_kv == 0 && h_first == 0 && lane == 0) maskA[sl] = tp.vmask;
+  };
+  SubTile t_half;
+  if (HALF) t_half = fetch_half(0);
+  if (!HALF && st < st_end) {
+    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
     if (t.vmask != 0u) {
       if (PIPE) {
         fetch_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, lane, rk);
         fetch_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, lane, rv);
+      } else if (SHARED) {
+        if (load_k)
+          issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+        else
+          issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
       } else {
         issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
         issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
       }
     }
   }
-  if (SHARED && lane == 0) maskA[wave] = t.vmask;
+  if (SHARED && !HALF && load_k && lane == 0) maskA[slot] = t.vmask;
   FOCUS_STAMP(2);
   bf16x8 q[1][G::kKSteps];
   load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
@@ -541,37 +667,65 @@ __global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_ke
     return e;
   };
   auto locate = [&](int sub) {
-    return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink);
+    return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
   };
   if (PIPE && t.vmask != 0u) {  // the first sub-tile: registers -> this wavefront's slot of buffer A
     store_subtile<D>(stageK, lane, rk);
     store_subtile<D>(stageV, lane, rv);
   }
-  if (SHARED) {
+  if (HALF) {
+    // Half rounds: while two slots are multiplied (wavefront w: slot pair's member w / 4, for query tile w % 4), the
+    // rows of the next two sub-tiles are on their way into registers; they are stored into the other two slots, which
+    // the previous half round has finished with, before the barrier that opens the next half round.
+    store_half(0, t_half);
+    const int n_half = (st_end - st_begin + 1) / 2;  // uniform over the workgroup
+    for (int ph = 0; ph < n_half; ++ph) {
+      __syncthreads();  // half round ph is staged; everyone is done with half round ph - 1
+      SubTile tn = no_tile();
+      if (ph + 1 < n_half) tn = fetch_half(ph + 1);
+      const int sl = (2 * ph + kg) & (kWavesPerGroup - 1);
+      const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[sl]);
+      if (vm != 0u) {
+        const char* cK = ldsA + sl * kBufBytes;
+        consume(cK, cK + G::kStageBytes, vm);
+      }
+      if (ph + 1 < n_half) store_half(ph + 1, tn);
+    }
+  } else if (SHARED) {
     // One round = four staged sub-tiles.  Single-buffered: two workgroups share a compute unit, and while one waits
     // for its rows the other multiplies.
+    FOCUS_LAP_START(lap);
     for (int base = st_begin; base < st_end; base += kWavesPerGroup) {  // uniform over the workgroup
-      wait_loads();     // this wavefront's slot of the round has landed ...
+      wait_loads();     // this wavefront's half slot of the round has landed ...
+      FOCUS_LAP(11, lap);
       __syncthreads();  // ... and so has everyone's
-      uint32_t vm[QT];
+      FOCUS_LAP(12, lap);
+      uint32_t vm[NS];
 #pragma unroll
-      for (int j = 0; j < QT; ++j) vm[j] = __builtin_amdgcn_readfirstlane(maskA[kg + j * KG]);
+      for (int j = 0; j < NS; ++j) vm[j] = __builtin_amdgcn_readfirstlane(maskA[kg + j * KG]);
+      // where the next round's sub-tile lives is looked up now, so that the dependent index loads finish in the
+      // shadow of the multiplications
+      const int st_n = base + kWavesPerGroup + slot;
+      SubTile tn = no_tile();
+      if (st_n < st_end) tn = locate(st_n);
 #pragma unroll
-      for (int j = 0; j < QT; ++j) {
+      for (int j = 0; j < NS; ++j) {
         if (vm[j] != 0u) {
           const char* cK = ldsA + (kg + j * KG) * kBufBytes;
           consume(cK, cK + G::kStageBytes, vm[j]);
         }
       }
+      FOCUS_LAP(13, lap);
       __syncthreads();  // everyone is done with the slots and their masks
-      const int st_n = base + kWavesPerGroup + wave;
-      SubTile tn = no_tile();
-      if (st_n < st_end) tn = locate(st_n);
-      if (lane == 0) maskA[wave] = tn.vmask;
+      FOCUS_LAP(14, lap);
+      if (load_k && lane == 0) maskA[slot] = tn.vmask;
       if (tn.vmask != 0u) {
-        issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, stageK, lane);
-        issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, stageV, lane);
+        if (load_k)
+          issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, stageK, lane);
+        else
+          issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, stageV, lane);
       }
+      FOCUS_LAP(15, lap);
     }
   } else if (!PIPE) {
     while (st < st_end) {
@@ -617,29 +771,31 @@ __global__ __launch_bounds__(256, ((FUSE & 2) == 0 ? 2 : 1)) void sparse_attn_ke
   }
   FOCUS_STAMP(7);
 
-  // ---- merge the wavefronts that share a query tile through each wavefront's own LDS slice
-  float* myO = reinterpret_cast<float*>(stageK);               // [16][D]
-  float* myML = reinterpret_cast<float*>(stageK + 16 * D * 4);  // [16][2]
-  constexpr int kPerThread = D / 16;                            // output columns per thread in the merge
+  // ---- merge the wavefronts that share a query tile through LDS (the stages are free by now)
+  float* myO = reinterpret_cast<float*>(ldsA + wave * kMergeBytes);  // [16][D]
+  constexpr int kPerThread = D / 16;                                  // output columns per thread in the merge
   constexpr int kVec = kPerThread / 4;
-  const int mq = threadIdx.x >> 4;                              // query of the tile this thread merges
+  constexpr int kTilesPerPass = W / kWavesPerGroup;                   // 256 threads merge one query tile
+  const int mq = (threadIdx.x >> 4) & 15;                             // query of the tile this thread merges
   const int mc = (threadIdx.x & 15) * kPerThread;
   wait_loads();
   __syncthreads();  // every staged sub-tile has been consumed by everyone
 #pragma unroll
   for (int ct = 0; ct < G::kColTiles; ++ct) *reinterpret_cast<floatx4*>(myO + c * D + ct * 16 + 4 * g) = o[ct];
-  if (g == 0) *reinterpret_cast<float2*>(myML + 2 * c) = make_float2(m_run, l_run);
+  if (g == 0) ml_sh[wave][c] = make_float2(m_run, l_run);
   __syncthreads();
 #pragma unroll
-  for (int tq = 0; tq < QT; ++tq) {
+  for (int pass = 0; pass < QT / kTilesPerPass; ++pass) {
+    const int tq = pass * kTilesPerPass + (threadIdx.x >> 8);
     float2 ml[KG];
     float4 ow[KG][kVec];
 #pragma unroll
     for (int k = 0; k < KG; ++k) {
-      const char* wbase = ldsA + (tq + QT * k) * kBufBytes;
-      ml[k] = *reinterpret_cast<const float2*>(wbase + 16 * D * 4 + 8 * mq);
+      const int w = tq + QT * k;  // the wavefronts of query tile tq
+      ml[k] = ml_sh[w][mq];
 #pragma unroll
-      for (int i = 0; i < kVec; ++i) ow[k][i] = *reinterpret_cast<const float4*>(wbase + (mq * D + mc + 4 * i) * 4);
+      for (int i = 0; i < kVec; ++i)
+        ow[k][i] = *reinterpret_cast<const float4*>(ldsA + w * kMergeBytes + (mq * D + mc + 4 * i) * 4);
     }
     float mmax = ml[0].x;
 #pragma unroll
@@ -704,15 +860,16 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
 template <int D, int QT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  const bool pipe = QT == 1 && p.pipelined;  // with shared sub-tiles (QT > 1) the rounds are always double-buffered
+  const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) are single-buffered, eight wavefronts
+  const dim3 block(QT > 1 ? 512 : 256);
   if (fused && pipe)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 3 : 1)>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 3 : 1)>), grid, block, 0, st, a);
   else if (fused)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 1>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 1>), grid, block, 0, st, a);
   else if (pipe)
-    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 2 : 0)>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 2 : 0)>), grid, block, 0, st, a);
   else
-    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 0>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 0>), grid, block, 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,

@@ -173,7 +173,7 @@ __device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, i
   const bool myvalid = tid < n && keyfn(tid, mykey);
   const uint32_t key1 = myvalid ? mykey + 1u : 0u;  // threads past n hold 0: not a candidate
   const int n_waves = nt >> 6;
-  if (MAXN <= 256 && n_waves <= 4 && max(k, 0) * n_waves <= kWave) {
+  if (MAXN <= 256 && max(k, 0) * n_waves <= kWave) {
     uint32_t pos, cnt;
     const bool sel = wave_select1(key1, k, pos, cnt);
     if (n_waves == 1) {  // a single wavefront: no LDS, no barrier
