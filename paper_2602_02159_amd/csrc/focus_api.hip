@@ -57,7 +57,7 @@ SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n
   // queries): fewer, longer workgroups with double-buffered key loops.  One sub-tile per wavefront (the 3 % keep
   // configurations): nothing to overlap.
   if (p.q_tiles_per_group > 1) {
-    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 1024));
+    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 512));  // two resident workgroups per compute unit
   } else if (p.per_split > kWavesPerGroup && env_int("FOCUS_ATTN_PIPE", 1) == 1) {
     plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 512));
     p.pipelined = p.per_split > kWavesPerGroup;

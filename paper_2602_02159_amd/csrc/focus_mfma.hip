@@ -38,20 +38,8 @@ __device__ long long* g_stamps;
       g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (i)] = \
           (i) == 0 ? wall_clock64() : clock64();                                                                \
   } while (0)
-#define FOCUS_LAP_START(t0) long long t0 = clock64()
-// accumulates clock64() - t0 into slot i of the wavefront's stamp row and restarts t0
-#define FOCUS_LAP(i, t0)                                                                                        \
-  do {                                                                                                          \
-    const long long now_ = clock64();                                                                           \
-    if ((threadIdx.x & 63) == 0)                                                                                \
-      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (i)] += \
-          now_ - (t0);                                                                                          \
-    (t0) = now_;                                                                                                \
-  } while (0)
 #else
 #define FOCUS_STAMP(i)
-#define FOCUS_LAP_START(t0)
-#define FOCUS_LAP(i, t0)
 #endif
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -96,13 +84,14 @@ __device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xfffffff
 // list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r.
 //   "inside a kept block": one look-up in `kept_bits` (bit b set <=> block b is kept; LDS, built by the workgroup)
 //   when that is given, else the block list is scanned 64 entries per load.
-//   "listed earlier": a strictly ascending list (what focus_find_sinks writes) cannot repeat an entry, which a scan
-//   of 64 entries per step establishes; only other lists pay for the all-pairs comparison.
+//   "listed earlier": a strictly ascending list (what focus_find_sinks writes) cannot repeat an entry; `ascending`
+//   says so (1 / 0, established once by the workgroup), or -1: not known, then a scan of 64 entries per step
+//   establishes it here.  Only lists that are not ascending pay for the all-pairs comparison.
 constexpr int kBitmapBlocks = 8192;  // largest n_b for which workgroups keep a bitmap of the kept blocks
 __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
                                                   const int32_t* __restrict__ kept_blocks, int n_keep,
                                                   const int32_t* __restrict__ sink_idx, int n_sink,
-                                                  const uint32_t* kept_bits = nullptr) {
+                                                  const uint32_t* kept_bits = nullptr, int ascending = -1) {
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
@@ -148,14 +137,16 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
     }
   }
   const int e_end = min(t.row0 + kSubTile, n_sink);
-  bool ascending = true;  // sink_idx[0 .. e_end) strictly ascending?
-  for (int j0 = 0; j0 + 1 < e_end; j0 += kWave) {
-    const int idx = j0 + lane;
-    const bool pair = idx + 1 < e_end;
-    const int a = pair ? sink_idx[idx] : 0, b = pair ? sink_idx[idx + 1] : 1;
-    if (__ballot(b <= a) != 0ull) ascending = false;
+  if (ascending < 0) {  // sink_idx[0 .. e_end) strictly ascending?
+    ascending = 1;
+    for (int j0 = 0; j0 + 1 < e_end; j0 += kWave) {
+      const int idx = j0 + lane;
+      const bool pair = idx + 1 < e_end;
+      const int a = pair ? sink_idx[idx] : 0, b = pair ? sink_idx[idx + 1] : 1;
+      if (__ballot(b <= a) != 0ull) ascending = 0;
+    }
   }
-  if (!ascending) {
+  if (ascending == 0) {
     for (int j0 = 0; j0 < e_end; j0 += kWave) {
       const int idx = j0 + lane;
       const int v = idx < e_end ? sink_idx[idx] : -2;
@@ -472,12 +463,14 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
 // QT = 1 (up to 16 active queries), four wavefronts: every wavefront owns its slot end to end — it stages the
 //   sub-tile, multiplies it against the one query tile and keeps its own running softmax; the four states are merged
 //   at the end.
-// QT = 2 / 4 (17..32 / 33..64 active queries per group), eight wavefronts: the staged sub-tiles are shared.
-//   Wavefronts 0..3 load the K rows of slots 0..3, wavefronts 4..7 the V rows; wavefront w then works for query tile
-//   w % QT on the slots w / QT, w / QT + 8 / QT, ...  Every K/V byte is still fetched once per workgroup, every
-//   wavefront carries the accumulators of ONE query tile, and two workgroups per compute unit put four wavefronts on
-//   each SIMD: a lone wavefront cannot hide the LDS and MFMA latencies of its own chain (measured: ~1 us per
-//   sub-tile and query tile, four times the arithmetic).
+// QT = 2 / 4 (17..32 / 33..64 active queries per group), four / eight wavefronts: the staged sub-tiles are shared and
+//   the key axis advances in half rounds of two sub-tiles.  Wavefront w works for query tile w % QT on member
+//   w / QT of the half round's slot pair; meanwhile the rows of the next two sub-tiles travel into registers (each
+//   wavefront fetches its share: one K or V tile with four wavefronts, half of one with eight) and are stored into
+//   the other slot pair once the previous half round has released it.  Every K/V byte is still fetched once per
+//   workgroup, every wavefront carries the accumulators of ONE query tile, and two workgroups per compute unit put
+//   2 (QT = 2) or 4 (QT = 4) wavefronts on each SIMD: a lone wavefront cannot hide the LDS and MFMA latencies of its
+//   own chain (measured: ~1 us per sub-tile and query tile, four times the arithmetic).
 //
 // FUSE bit 0 clear: kept_blocks comes from memory.
 // FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
@@ -488,18 +481,17 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
 // In every case a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
 // behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
 template <int D, int QT, int FUSE>
-__global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 0 ? 2 : 1))) void sparse_attn_kernel(
+__global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) == 0 ? 2 : 1))) void sparse_attn_kernel(
     const AttnArgs p) {
   using G = Geo<D>;
   constexpr bool FUSED = (FUSE & 1) != 0;                // Top-C in the prologue
   constexpr bool SHARED = QT > 1;                        // staged sub-tiles are shared by the wavefronts
   constexpr bool PIPE = (FUSE & 2) != 0;                 // QT = 1 only: two K/V stages per wavefront
-  static_assert(!(PIPE && SHARED), "shared sub-tiles are single-buffered");
-  constexpr int W = SHARED ? 2 * kWavesPerGroup : kWavesPerGroup;  // wavefronts in the workgroup
+  static_assert(!(PIPE && SHARED), "shared sub-tiles have their own pipelining");
+  constexpr int W = QT == 4 ? 2 * kWavesPerGroup : kWavesPerGroup;  // wavefronts in the workgroup
   constexpr int KG = W / QT;                             // wavefronts per query tile, each on its own slots
-  constexpr int NS = kWavesPerGroup / KG;                // slots a wavefront multiplies per round (SHARED)
-  constexpr bool HALF = QT == 4;                         // SHARED in half rounds: two slots multiplied, two refilled
-  constexpr int NLH = G::kLoads / 2;                     // HALF: loads per wavefront and half round
+  constexpr int NLH = G::kLoads / (W / kWavesPerGroup);  // SHARED: loads per wavefront and half round
+  static_assert(!SHARED || KG == 2, "a half round holds two sub-tiles");
   constexpr int kBufBytes = 2 * G::kStageBytes;          // one slot: K stage + V stage of a sub-tile
   constexpr int kMergeBytes = 16 * D * 4;                // one wavefront's O tile in the final merge
   static_assert(QT == 1 || QT == 2 || QT == 4, "query tiles per workgroup");
@@ -519,10 +511,9 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
   FOCUS_STAMP(0);
   FOCUS_STAMP(1);
 
-  const int slot = wave & (kWavesPerGroup - 1);  // the slot this wavefront stages
+  const int slot = wave & (kWavesPerGroup - 1);  // QT = 1: the slot this wavefront owns
   char* stageK = ldsA + slot * kBufBytes;
   char* stageV = stageK + G::kStageBytes;
-  const bool load_k = !SHARED || wave < kWavesPerGroup;  // SHARED: wavefronts 0..3 stage K rows, 4..7 V rows
   const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
   const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
   const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
@@ -552,22 +543,32 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
     kept_blocks = kept_sh;
   }
 
-  // Workgroups whose key range reaches the sink sub-tiles keep a bitmap of the kept blocks for the union of Eq. 8.
+  // Workgroups whose key range reaches the sink sub-tiles prepare the union of Eq. 8 once: a bitmap of the kept
+  // blocks, and whether the sink list is strictly ascending (then it cannot name a position twice).
   __shared__ uint32_t kept_bits_sh[kBitmapBlocks / 32];
+  __shared__ int sinks_unsorted_sh;
   const uint32_t* kept_bits = nullptr;
+  int sinks_ascending = -1;
   {
     const int first_sink_sub = p.n_keep * p.sub_per_block + (p.N + kSubTile - 1) / kSubTile;
     const int my_end = min((int)(blockIdx.x + 1) * p.per_split, p.n_sub);
-    if (p.n_sink > 0 && p.n_keep > 0 && p.n_b <= kBitmapBlocks && my_end > first_sink_sub) {  // uniform over the workgroup
-      const int words = (p.n_b + 31) >> 5;
+    if (p.n_sink > 0 && my_end > first_sink_sub) {  // uniform over the workgroup
+      const bool bitmap = p.n_keep > 0 && p.n_b <= kBitmapBlocks;
+      const int words = bitmap ? (p.n_b + 31) >> 5 : 0;
       for (int i = threadIdx.x; i < words; i += blockDim.x) kept_bits_sh[i] = 0u;
+      if (threadIdx.x == 0) sinks_unsorted_sh = 0;
       __syncthreads();
-      for (int i = threadIdx.x; i < p.n_keep; i += blockDim.x) {
-        const int b = kept_blocks[i];
-        if (b >= 0 && b < p.n_b) atomicOr(&kept_bits_sh[b >> 5], 1u << (b & 31));
+      if (bitmap) {
+        for (int i = threadIdx.x; i < p.n_keep; i += blockDim.x) {
+          const int b = kept_blocks[i];
+          if (b >= 0 && b < p.n_b) atomicOr(&kept_bits_sh[b >> 5], 1u << (b & 31));
+        }
       }
+      for (int i = threadIdx.x; i + 1 < p.n_sink; i += blockDim.x)
+        if (p.sink_idx[i + 1] <= p.sink_idx[i]) sinks_unsorted_sh = 1;
       __syncthreads();
-      kept_bits = kept_bits_sh;
+      if (bitmap) kept_bits = kept_bits_sh;
+      sinks_ascending = sinks_unsorted_sh ? 0 : 1;
     }
   }
 
@@ -582,7 +583,7 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
   t.row0 = 0;
   t.vmask = 0u;
   uintx4 rk[G::kLoads], rv[G::kLoads];  // PIPE: the sub-tile in flight
-  // HALF: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
+  // SHARED: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
   // the half round's sub-tile (w & 1)
   const int h_i = wave & 1, h_kv = (wave >> 1) & 1, h_first = (wave >> 2) * NLH;
   uintx4 rh[NLH];
@@ -593,7 +594,8 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
     tp.vmask = 0u;
     const int sub = st_begin + 2 * ph + h_i;
     if (sub < st_end)
-      tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
+      tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
+                          sinks_ascending);
     if (tp.vmask != 0u)
       fetch_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink, lane, h_first, rh);
     return tp;
@@ -605,25 +607,20 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
     if (h_kv == 0 && h_first == 0 && lane == 0) maskA[sl] = tp.vmask;
   };
   SubTile t_half;
-  if (HALF) t_half = fetch_half(0);
-  if (!HALF && st < st_end) {
-    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
+  if (SHARED) t_half = fetch_half(0);
+  if (!SHARED && st < st_end) {
+    t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
+                          sinks_ascending);
     if (t.vmask != 0u) {
       if (PIPE) {
         fetch_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, lane, rk);
         fetch_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, lane, rv);
-      } else if (SHARED) {
-        if (load_k)
-          issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-        else
-          issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
       } else {
         issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
         issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
       }
     }
   }
-  if (SHARED && !HALF && load_k && lane == 0) maskA[slot] = t.vmask;
   FOCUS_STAMP(2);
   bf16x8 q[1][G::kKSteps];
   load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
@@ -667,65 +664,35 @@ __global__ __launch_bounds__((QT > 1 ? 512 : 256), (QT > 1 ? 4 : ((FUSE & 2) == 
     return e;
   };
   auto locate = [&](int sub) {
-    return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits);
+    return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
+                          sinks_ascending);
   };
   if (PIPE && t.vmask != 0u) {  // the first sub-tile: registers -> this wavefront's slot of buffer A
     store_subtile<D>(stageK, lane, rk);
     store_subtile<D>(stageV, lane, rv);
   }
-  if (HALF) {
+  if (SHARED) {
     // Half rounds: while two slots are multiplied (wavefront w: slot pair's member w / 4, for query tile w % 4), the
     // rows of the next two sub-tiles are on their way into registers; they are stored into the other two slots, which
-    // the previous half round has finished with, before the barrier that opens the next half round.
+    // the previous half round has finished with, before the barrier that opens the next half round.  Loads are in
+    // flight all the time: a request is issued as soon as the registers of the previous one have been stored.
     store_half(0, t_half);
     const int n_half = (st_end - st_begin + 1) / 2;  // uniform over the workgroup
+    SubTile tn = no_tile();
+    if (1 < n_half) tn = fetch_half(1);
     for (int ph = 0; ph < n_half; ++ph) {
       __syncthreads();  // half round ph is staged; everyone is done with half round ph - 1
-      SubTile tn = no_tile();
-      if (ph + 1 < n_half) tn = fetch_half(ph + 1);
       const int sl = (2 * ph + kg) & (kWavesPerGroup - 1);
       const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[sl]);
       if (vm != 0u) {
         const char* cK = ldsA + sl * kBufBytes;
         consume(cK, cK + G::kStageBytes, vm);
       }
-      if (ph + 1 < n_half) store_half(ph + 1, tn);
-    }
-  } else if (SHARED) {
-    // One round = four staged sub-tiles.  Single-buffered: two workgroups share a compute unit, and while one waits
-    // for its rows the other multiplies.
-    FOCUS_LAP_START(lap);
-    for (int base = st_begin; base < st_end; base += kWavesPerGroup) {  // uniform over the workgroup
-      wait_loads();     // this wavefront's half slot of the round has landed ...
-      FOCUS_LAP(11, lap);
-      __syncthreads();  // ... and so has everyone's
-      FOCUS_LAP(12, lap);
-      uint32_t vm[NS];
-#pragma unroll
-      for (int j = 0; j < NS; ++j) vm[j] = __builtin_amdgcn_readfirstlane(maskA[kg + j * KG]);
-      // where the next round's sub-tile lives is looked up now, so that the dependent index loads finish in the
-      // shadow of the multiplications
-      const int st_n = base + kWavesPerGroup + slot;
-      SubTile tn = no_tile();
-      if (st_n < st_end) tn = locate(st_n);
-#pragma unroll
-      for (int j = 0; j < NS; ++j) {
-        if (vm[j] != 0u) {
-          const char* cK = ldsA + (kg + j * KG) * kBufBytes;
-          consume(cK, cK + G::kStageBytes, vm[j]);
-        }
+      if (ph + 1 < n_half) {  // the rows requested a whole half round ago go into the slots freed by half round ph - 1,
+        store_half(ph + 1, tn);  // and the registers take the request after next straight away
+        tn = no_tile();
+        if (ph + 2 < n_half) tn = fetch_half(ph + 2);
       }
-      FOCUS_LAP(13, lap);
-      __syncthreads();  // everyone is done with the slots and their masks
-      FOCUS_LAP(14, lap);
-      if (load_k && lane == 0) maskA[slot] = tn.vmask;
-      if (tn.vmask != 0u) {
-        if (load_k)
-          issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, stageK, lane);
-        else
-          issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, stageV, lane);
-      }
-      FOCUS_LAP(15, lap);
     }
   } else if (!PIPE) {
     while (st < st_end) {
@@ -860,8 +827,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
 template <int D, int QT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) are single-buffered, eight wavefronts
-  const dim3 block(QT > 1 ? 512 : 256);
+  const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) have their own pipelining
+  const dim3 block(QT == 4 ? 512 : 256);
   if (fused && pipe)
     hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 3 : 1)>), grid, block, 0, st, a);
   else if (fused)
