@@ -109,11 +109,17 @@ static ScoreWs ws_block_scores(const focus_shape& s) {
 struct SinkWs {
   size_t logits, part_ml, lse2, col_mass, cand, total;
 };
+// At most 16 active queries: one pass over K that spills the scaled logits (64 bytes per key and head), which the
+// column-mass kernel re-reads.  More: the spill would outweigh K itself, so K is scanned twice — statistics first,
+// then probabilities summed over the queries on the fly — and only [q_groups * H, L] column sums are stored.
+static bool sinks_two_pass(const SplitPlan& p) { return p.q_pad > 16; }
+
 static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
   SinkWs w;
   const size_t L = (size_t)s.n_ctx + s.n_resp;
-  w.logits = 0;
-  size_t off = align_up((size_t)s.n_heads * L * p.q_pad * sizeof(float));
+  w.logits = 0;  // logits [H, L, 16], or column sums [q_groups * H, L]
+  size_t off = align_up(sinks_two_pass(p) ? (size_t)p.q_groups * s.n_heads * L * sizeof(float)
+                                          : (size_t)s.n_heads * L * p.q_pad * sizeof(float));
   w.part_ml = off;
   off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
   w.lse2 = off;
@@ -296,14 +302,21 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   float* lse2 = reinterpret_cast<float*>(ws + w.lse2);
   float* S = col_mass ? col_mass : reinterpret_cast<float*>(ws + w.col_mass);
   const int L = shape->n_ctx + shape->n_resp;
-  hipError_t e = launch_qk_logits(Q, active_idx, counts, max_active, K, *shape, p, logits, part_ml, st);
+  const bool two_pass = sinks_two_pass(p);
+  hipError_t e = launch_qk_logits(Q, active_idx, counts, max_active, K, *shape, p, two_pass ? 1 : 0, logits, part_ml, nullptr,
+                                  nullptr, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(logits)", e);
   e = launch_lse_combine(part_ml, shape->n_heads, p.q_pad, p.n_split, lse2, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(lse)", e);
+  if (two_pass) {
+    e = launch_qk_logits(Q, active_idx, counts, max_active, K, *shape, p, 2, nullptr, nullptr, lse2, logits, st);
+    if (e != hipSuccess) return launch_fail("focus_find_sinks(column sums)", e);
+  }
   // few sinks: the column-mass groups nominate, one small workgroup decides; many sinks: radix select over all of S
   const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
   int32_t* cand = tournament ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
-  e = launch_column_mass(logits, lse2, counts, max_active, shape->n_heads, L, p.q_pad, S, shape->n_ctx, n_sink, cand, st);
+  e = launch_column_mass(logits, two_pass, lse2, counts, max_active, two_pass ? p.q_groups * shape->n_heads : shape->n_heads,
+                         shape->n_heads, L, S, shape->n_ctx, n_sink, cand, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
   if (tournament) {
     e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);

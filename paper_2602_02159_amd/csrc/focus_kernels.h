@@ -50,16 +50,19 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
 constexpr int kTournamentMaxSinks = 16;
 constexpr int kTournamentMaxCand = 4096;  // ceil(M / 128) * n_sink
 bool sink_tournament_fits(int M, int n_sink);
-// cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits)
-hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active,
-                              int H, int L, int q_pad, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st);
+// cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits).
+// pre_reduced = false: src = scaled logits [H, L, 16] of at most 16 queries, n_parts = H;
+// pre_reduced = true:  src = column sums [n_parts, L] from the second pass over K.
+hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
+                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st);
 hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st);
 
 // ---- MFMA kernels (focus_mfma.hip)
+// mode 0: logits [H, L, q_pad] + part_ml out; mode 1: part_ml out only; mode 2: lse2 in, colpart [q_groups * H, L] out
 hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
-                            const void* K, const focus_shape& s, const SplitPlan& p, float* logits, float* part_ml,
-                            hipStream_t st);
+                            const void* K, const focus_shape& s, const SplitPlan& p, int mode, float* logits,
+                            float* part_ml, const float* lse2, float* colpart, hipStream_t st);
 // Extra arguments of the fused layer path: the attention kernel ranks the blocks itself from the per-head partial
 // relevances (n_b <= kFusedMaxBlocks).
 constexpr int kFusedMaxBlocks = 256;

@@ -895,15 +895,32 @@ struct LogitArgs {
   const uint16_t* K;
   const int32_t* active_idx;
   const int32_t* counts;
-  float* logits;   // [H, L, q_pad]
-  float* part_ml;  // [H, q_pad, n_split, 2]
+  float* logits;      // [H, L, q_pad]                         (mode 0)
+  float* part_ml;     // [H, q_pad, n_split, 2]                (modes 0, 1)
+  const float* lse2;  // [H, q_pad] base-2 log-sum-exp per row (mode 2)
+  float* colpart;     // [q_groups * H, L]                     (mode 2)
   int64_t qsh, qsn, ksh, ksn;
   int H, L, n_gen, max_active;
   int n_sub, per_split, n_split, q_pad;
   float scale_log2;
 };
 
-template <int D, int NQT>
+// sum of x over the 16 lanes of a DPP row (the lanes that hold the 16 queries of a tile for the same keys); every
+// lane of the row receives the total
+__device__ __forceinline__ float row_sum16(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, false));  // row_half_mirror
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, false));  // row_mirror
+  return x;
+}
+
+// MODE 0: the scaled logits are written out (for up to 16 queries re-reading 64 bytes per key and head is cheaper
+//         than a second pass over K) together with the per-split softmax statistics.
+// MODE 1: statistics only.
+// MODE 2: second pass for more than 16 queries: with the row log-sum-exps known, the probabilities are formed on the
+//         fly and summed over the workgroup's queries; colpart[qg * H + h, j] = sum_i P[h, i, j].
+template <int D, int NQT, int MODE>
 __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
   using G = Geo<D>;
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerGroup * G::kStageBytes];
@@ -942,10 +959,17 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
   for (int qt = 0; qt < NQT; ++qt) mask_q_tile<D>(q[qt], q_base + qt * kQTile, n_act, lane);
 
   float m_run[NQT], l_run[NQT];
+  float neg_lse[NQT];  // MODE 2: minus the row's log-sum-exp; -inf for rows that do not exist
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) {
     m_run[qt] = -INFINITY;
     l_run[qt] = 0.f;
+    neg_lse[qt] = 0.f;
+    if (MODE == 2) {
+      const int a = q_base + qt * kQTile + c;
+      const float z = p.lse2[(int64_t)h * p.q_pad + a];
+      neg_lse[qt] = (a < n_act && z < INFINITY) ? -z : -INFINITY;  // exp2(x - inf) = 0: the row contributes nothing
+    }
   }
 
   while (st < st_end) {
@@ -953,24 +977,49 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
     wait_loads();
     floatx4 acc[NQT][2];
     qk_subtile<D, NQT>(acc, stageK, q, lane);
-    // the staged rows are consumed: the next sub-tile can stream in while the logits are written
+    // the staged rows are consumed: the next sub-tile can stream in while the results are written
     st += kWavesPerGroup;
     if (st < st_end) {
       t = tile_of(st);
       issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
     }
+    if (MODE == 2) {
+      float colsum[8];
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      float ps[8];
-      softmax_step(acc[qt], cur.vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
-      float* dst = p.logits + ((int64_t)h * p.L + cur.row0) * p.q_pad + q_base + qt * kQTile + c;
+      for (int e = 0; e < 8; ++e) colsum[e] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-        if ((cur.vmask >> slot) & 1u) dst[(int64_t)slot * p.q_pad] = acc[qt][e >> 2][e & 3] * p.scale_log2;
+      for (int qt = 0; qt < NQT; ++qt) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          colsum[e] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[qt][e >> 2][e & 3], p.scale_log2, neg_lse[qt]));
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) colsum[e] = row_sum16(colsum[e]);
+      if (c == 0) {
+        float* dst = p.colpart + ((int64_t)qg * p.H + h) * p.L + cur.row0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
+          if ((cur.vmask >> slot) & 1u) dst[slot] = colsum[e];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt) {
+        float ps[8];
+        softmax_step(acc[qt], cur.vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
+        if (MODE == 0) {
+          float* dst = p.logits + ((int64_t)h * p.L + cur.row0) * p.q_pad + q_base + qt * kQTile + c;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
+            if ((cur.vmask >> slot) & 1u) dst[(int64_t)slot * p.q_pad] = acc[qt][e >> 2][e & 3] * p.scale_log2;
+          }
+        }
       }
     }
   }
+  if (MODE == 2) return;
 
   if (g == 0) {
 #pragma unroll
@@ -998,15 +1047,21 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
 }
 
 template <int D, int NQT>
-static hipError_t launch_logits_t(const LogitArgs& a, const SplitPlan& p, hipStream_t st) {
+static hipError_t launch_logits_t(const LogitArgs& a, const SplitPlan& p, int mode, hipStream_t st) {
   dim3 grid(p.n_split, a.H, p.q_groups);
-  hipLaunchKernelGGL((qk_logits_kernel<D, NQT>), grid, dim3(256), 0, st, a);
+  if (mode == 0)
+    hipLaunchKernelGGL((qk_logits_kernel<D, NQT, 0>), grid, dim3(256), 0, st, a);
+  else if (mode == 1)
+    hipLaunchKernelGGL((qk_logits_kernel<D, NQT, 1>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((qk_logits_kernel<D, NQT, 2>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
+// mode 0: logits + part_ml out; mode 1: part_ml out; mode 2: lse2 in, colpart out (see qk_logits_kernel)
 hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
-                            const void* K, const focus_shape& s, const SplitPlan& p, float* logits, float* part_ml,
-                            hipStream_t st) {
+                            const void* K, const focus_shape& s, const SplitPlan& p, int mode, float* logits,
+                            float* part_ml, const float* lse2, float* colpart, hipStream_t st) {
   LogitArgs a;
   a.Q = static_cast<const uint16_t*>(Q);
   a.K = static_cast<const uint16_t*>(K);
@@ -1014,6 +1069,8 @@ hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int3
   a.counts = counts;
   a.logits = logits;
   a.part_ml = part_ml;
+  a.lse2 = lse2;
+  a.colpart = colpart;
   a.qsh = s.q_stride_h; a.qsn = s.q_stride_n;
   a.ksh = s.k_stride_h; a.ksn = s.k_stride_n;
   a.H = s.n_heads; a.L = s.n_ctx + s.n_resp; a.n_gen = s.n_gen; a.max_active = max_active;
@@ -1021,13 +1078,13 @@ hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int3
   a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
   const int nqt = p.q_tiles_per_group;
   if (s.head_dim == 128) {
-    if (nqt == 1) return launch_logits_t<128, 1>(a, p, st);
-    if (nqt == 2) return launch_logits_t<128, 2>(a, p, st);
-    return launch_logits_t<128, 4>(a, p, st);
+    if (nqt == 1) return launch_logits_t<128, 1>(a, p, mode, st);
+    if (nqt == 2) return launch_logits_t<128, 2>(a, p, mode, st);
+    return launch_logits_t<128, 4>(a, p, mode, st);
   }
-  if (nqt == 1) return launch_logits_t<64, 1>(a, p, st);
-  if (nqt == 2) return launch_logits_t<64, 2>(a, p, st);
-  return launch_logits_t<64, 4>(a, p, st);
+  if (nqt == 1) return launch_logits_t<64, 1>(a, p, mode, st);
+  if (nqt == 2) return launch_logits_t<64, 2>(a, p, mode, st);
+  return launch_logits_t<64, 4>(a, p, mode, st);
 }
 
 }  // namespace focus

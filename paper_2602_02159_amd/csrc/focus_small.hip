@@ -376,40 +376,57 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
   return hipGetLastError();
 }
 
-// logits: [H, L, q_pad] fp32.  Workgroup = 128 keys x 4 head groups (512 threads); thread (key, hg) walks heads
-// hg, hg+4, ...  QP16 = true: q_pad == 16, the loads of four heads (16 x 16 bytes) are issued before the first exp2.
+// Column attention mass S_j (Eq. 6) from what the first stage left behind.  Workgroup = 128 keys x 4 part groups
+// (512 threads); thread (key, pg) walks parts pg, pg + 4, ...
+//   PRE = false: `src` holds the scaled logits [H, L, 16] fp32 of at most 16 active queries and lse2 their row
+//                log-sum-exps [H, 16]; a part is a head, its contribution sum_i exp2(logit - lse).  The loads of four
+//                heads (16 x 16 bytes) are issued before the first exp2.
+//   PRE = true:  `src` holds per-part column sums [n_parts, L] (already summed over a part's queries); they are
+//                added up, eight loads in flight.
+// S_j = total / (H * n_act).
 // With cand != nullptr (small N_sink) the workgroup also plays the first round of the sink tournament: the n_sink
 // largest masses among its own prompt positions (j < M; ties to the lower j) go to cand[wg * n_sink ..], ascending,
 // padded with -1.  The overall Top-N_sink is a subset of the union of these lists (sink_final_kernel).
 constexpr int kMassKeys = 128;
 
-template <bool QP16>
-__global__ __launch_bounds__(512) void column_mass_kernel(const float* __restrict__ logits, const float* __restrict__ lse2,
-                                                          const int32_t* __restrict__ counts, int max_active, int H, int L,
-                                                          int q_pad, float* __restrict__ col_mass, int M, int n_sink,
+template <bool PRE>
+__global__ __launch_bounds__(512) void column_mass_kernel(const float* __restrict__ src, const float* __restrict__ lse2,
+                                                          const int32_t* __restrict__ counts, int max_active, int n_parts,
+                                                          int H, int L, float* __restrict__ col_mass, int M, int n_sink,
                                                           int32_t* __restrict__ cand) {
   __shared__ float red[4][kMassKeys];
   __shared__ __attribute__((aligned(16))) uint32_t ckeys[256];
   __shared__ uint32_t ctotal;
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  const int kj = threadIdx.x & (kMassKeys - 1), hg = threadIdx.x / kMassKeys;
+  const int kj = threadIdx.x & (kMassKeys - 1), pg = threadIdx.x / kMassKeys;
   const int j = blockIdx.x * kMassKeys + kj;
   float acc = 0.f;
   if (j < L) {
-    if (QP16) {
-      for (int h0 = hg; h0 < H; h0 += 16) {
+    if (PRE) {
+      for (int q0 = pg; q0 < n_parts; q0 += 32) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int q = q0 + 4 * u;
+          x[u] = q < n_parts ? src[(int64_t)q * L + j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u];
+      }
+    } else {
+      for (int h0 = pg; h0 < n_parts; h0 += 16) {
         float4 x[4][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int h = h0 + 4 * u;
-          const float4* lp = reinterpret_cast<const float4*>(logits + ((int64_t)(h < H ? h : hg) * L + j) * 16);
+          const float4* lp = reinterpret_cast<const float4*>(src + ((int64_t)(h < n_parts ? h : pg) * L + j) * 16);
 #pragma unroll
           for (int i = 0; i < 4; ++i) x[u][i] = lp[i];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int h = h0 + 4 * u;
-          if (h < H) {
+          if (h < n_parts) {
             const float4* ls = reinterpret_cast<const float4*>(lse2 + (int64_t)h * 16);
             float a = 0.f;
 #pragma unroll
@@ -425,33 +442,18 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
           }
         }
       }
-    } else {
-      for (int h = hg; h < H; h += 4) {
-        const float* lp = logits + ((int64_t)h * L + j) * q_pad;
-        const float* ls = lse2 + (int64_t)h * q_pad;
-        float a = 0.f;
-        for (int i0 = 0; i0 < n_act; i0 += 4) {
-          const float4 x = *reinterpret_cast<const float4*>(lp + i0);
-          const float4 z = *reinterpret_cast<const float4*>(ls + i0);
-          a += __builtin_amdgcn_exp2f(x.x - z.x);
-          if (i0 + 1 < n_act) a += __builtin_amdgcn_exp2f(x.y - z.y);
-          if (i0 + 2 < n_act) a += __builtin_amdgcn_exp2f(x.z - z.z);
-          if (i0 + 3 < n_act) a += __builtin_amdgcn_exp2f(x.w - z.w);
-        }
-        acc += a;
-      }
     }
   }
-  red[hg][kj] = acc;
+  red[pg][kj] = acc;
   __syncthreads();
   float mass = 0.f;
-  if (hg == 0 && j < L) {
+  if (pg == 0 && j < L) {
     const float tot = (red[0][kj] + red[1][kj]) + (red[2][kj] + red[3][kj]);
     mass = n_act > 0 ? tot / ((float)H * (float)n_act) : 0.f;
     col_mass[j] = mass;
   }
   if (cand != nullptr && blockIdx.x * kMassKeys < M) {  // uniform over the workgroup
-    if (threadIdx.x < 256) ckeys[threadIdx.x] = (hg == 0 && j < M) ? order_key(mass) + 1u : 0u;
+    if (threadIdx.x < 256) ckeys[threadIdx.x] = (pg == 0 && j < M) ? order_key(mass) + 1u : 0u;
     __syncthreads();
     if (threadIdx.x < kWave)
       wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * kMassKeys);
@@ -500,15 +502,16 @@ bool sink_tournament_fits(int M, int n_sink) {
   return n_sink >= 1 && n_sink <= kTournamentMaxSinks && (int64_t)ceil_div(M, kMassKeys) * n_sink <= kTournamentMaxCand;
 }
 
-hipError_t launch_column_mass(const float* logits, const float* lse2, const int32_t* counts, int max_active, int H,
-                              int L, int q_pad, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st) {
+// pre_reduced = false: src = logits [H, L, 16], n_parts = H.  pre_reduced = true: src = column sums [n_parts, L].
+hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
+                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st) {
   if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
-  if (q_pad == 16)
-    hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, logits, lse2, counts,
-                       max_active, H, L, q_pad, col_mass, M, n_sink, cand);
+  if (pre_reduced)
+    hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, src, lse2, counts,
+                       max_active, n_parts, H, L, col_mass, M, n_sink, cand);
   else
-    hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, logits, lse2, counts,
-                       max_active, H, L, q_pad, col_mass, M, n_sink, cand);
+    hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, src, lse2, counts,
+                       max_active, n_parts, H, L, col_mass, M, n_sink, cand);
   return hipGetLastError();
 }
 
