@@ -4,9 +4,12 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stack32k]
 
 A "step" is one pass of the whole hot path over the 32-layer, 32K-context workload: query selection once,
-sink identification once at the probe layer (16), then for each of the 15 sparse layers (17..31) block means,
-block relevance + Top-C and the sparse attention.  All inputs are resident in HBM before the clock starts.
-Prints ONE JSON line; see DESIGN.md ("Measurement") for the meaning of every field.
+sink identification once at the probe layer (16), then for each of the 15 sparse layers (17..31) one
+focus_sparse_layer call (K scan -> block relevance, Top-C, sparse attention).  All inputs are resident in HBM
+before the clock starts.  Prints ONE JSON line: `value` = ms per step with nothing cached between steps; the same
+step with cached block means and with dense attention; per-stage microseconds, GB/s and TFLOP/s against the
+algorithmic bytes and flops; `roofline` for the stage with the largest share of the step; `cpu_baseline`: the
+float64 oracle timed on the host; `parity_vs_oracle`: a spot check of the timed buffers.
 """
 from __future__ import annotations
 
@@ -226,7 +229,8 @@ def main() -> int:
     H, d, L, M = w.n_heads, w.head_dim, w.n_kv, w.n_ctx
     n_b = w.n_blocks
 
-    # ---- algorithmic bytes / flops per launch of each stage (what the method must move; the design doc derives them)
+    # ---- algorithmic bytes / flops per launch of each stage: what the method must move, not what an implementation
+    # may add (the logits spilled, or K read a second time, while scoring the sinks are not counted)
     mean_keys = float(np.mean(n_keys))
     alg = {
         "select": {"bytes": w.n_gen * 5 + 4 * (w.k_focus + n_q + 2), "flops": 0},
@@ -335,8 +339,10 @@ def main() -> int:
     share = {s: stages[s]["us_per_launch"] * per_step_count[s] for s in in_step}
     dom_kernel = max(share, key=share.get)
     ds = stages[dom_kernel]
-    kernel_name = {"block_partials": "block_means_kernel<128, true>", "find_sinks": "qk_logits_kernel<128, 1>",
-                   "sparse_attn": "sparse_attn_kernel<128, 1, 1>", "select": "select_queries_kernel"}[dom_kernel]
+    qtw = 1 if n_q <= 16 else (2 if n_q <= 32 else 4)   # query tiles per workgroup the launchers pick
+    kernel_name = {"block_partials": f"block_means_kernel<{d}, true>",
+                   "find_sinks": f"qk_logits_kernel<{d}, {qtw}, {0 if qtw == 1 else 1}> and the rest of the sink chain",
+                   "sparse_attn": f"sparse_attn_kernel<{d}, {qtw}, 1>", "select": "select_queries_kernel"}[dom_kernel]
     # HBM traffic of that kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in a separate run of this
     # script (--mode pmc) and stored by --parse-pmc; scaled by the counters' reading for a 1 GiB copy
     traffic = None
@@ -345,7 +351,7 @@ def main() -> int:
             pmc = json.load(fh)
         # the counters are taken on the stand-alone stages; the attention kernel appears there without the fused Top-C
         # prologue (<128, 1, 0>), a name the dense comparison shares: its smallest dispatch is the sparse one
-        want = "sparse_attn_kernel<128, 1, 0>" if dom_kernel == "sparse_attn" else kernel_name
+        want = f"sparse_attn_kernel<{d}, {qtw}, 0>" if dom_kernel == "sparse_attn" else kernel_name.split(" and ")[0]
         which = "min" if dom_kernel == "sparse_attn" else "max"
         for name, v in pmc["kernels"].items():
             if want in name:
