@@ -296,6 +296,26 @@ def test_sparse_attn_is_deterministic_and_linear_in_v(G):
     assert torch.equal(o3.float(), o1.float() * 2)         # scaling by two is exact in bf16
 
 
+@pytest.mark.parametrize("n_act", [16, 30, 50])
+@pytest.mark.parametrize("ascending", [True, False])
+def test_sparse_attn_many_sinks_inside_and_outside_kept_blocks(G, n_act, ascending):
+    """Eq. 8 as a set with hundreds of sinks: about a third of them fall inside kept blocks and a few are listed twice;
+    an ascending list (what focus_find_sinks writes) and a shuffled one must both be attended exactly once."""
+    H, M, N, d, B, n_gen = 2, 8192, 48, 128, 64, 64
+    rng = np.random.default_rng(1000 + n_act)
+    n_b = M // B
+    kept = np.sort(rng.choice(n_b, 40, replace=False))
+    sinks = rng.choice(M, 200, replace=False)
+    sinks = np.concatenate([sinks, sinks[:7]])                  # seven positions named twice
+    sinks = np.sort(sinks) if ascending else rng.permutation(sinks)
+    inside = np.isin(sinks // B, kept).sum()
+    assert 30 < inside < 120
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    out, lse, ref, ref_lse = _attn_case(G, H, M, N, d, B, n_gen, active, kept, sinks, seed=70)
+    G.assert_attention_close(out, ref)
+    assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
+
+
 # ------------------------------------------------------------------------------------------------ fused layer call
 @pytest.mark.parametrize("H,M,N,d,B,n_gen,n_f,n_act,n_keep,n_sink", [
     (4, 1024, 32, 64, 64, 32, 8, 8, 4, 2),
@@ -304,6 +324,10 @@ def test_sparse_attn_is_deterministic_and_linear_in_v(G):
     (2, 16384, 64, 128, 64, 64, 16, 16, 25, 4),       # exactly 256 blocks: the largest fused case
     (2, 8192, 64, 128, 16, 64, 16, 16, 40, 4),        # 512 blocks: falls back to the separate kernels
     (2, 2048, 0, 64, 128, 16, 3, 16, 16, 0),          # every block kept, no response rows, no sinks
+    (4, 4096, 64, 128, 64, 64, 8, 28, 20, 6),         # two query tiles per workgroup, Top-C inside the kernel
+    (4, 2048, 32, 64, 32, 80, 8, 72, 30, 40),         # five query tiles (two groups of four), d = 64, unsorted sinks
+    (3, 1500, 10, 64, 50, 40, 4, 20, 12, 33),         # two query tiles, d = 64, ragged blocks
+    (2, 16384, 64, 128, 64, 64, 4, 36, 128, 163),     # the paper's proportions at 16K: half the blocks, 1 % sinks
 ])
 def test_sparse_layer_equals_block_scores_then_sparse_attn(G, H, M, N, d, B, n_gen, n_f, n_act, n_keep, n_sink):
     rng = np.random.default_rng(M + n_keep)
