@@ -187,7 +187,7 @@ def main() -> int:
     steps_obj = []
     for s in range(args.sets):
         ws_ = w.with_(seed=w.seed + 7919 * s)
-        probe = fi.layer_qkv(ws_, probe_layer, dev, which="qk")
+        probe = fi.layer_qkv(ws_, probe_layer, dev, which="qkv")
         layers = [fi.layer_qkv(ws_, l, dev) for l in sparse_ids]
         steps_obj.append(FocusStep(conf, masked, probe, layers, w.n_ctx, w.block, w.k_focus, w.window, w.n_keep, w.n_sink))
     torch.cuda.synchronize()
@@ -206,7 +206,8 @@ def main() -> int:
         st = steps_obj[0]
         st.run()
         sync()
-        for stage in ("block_means", "block_partials", "block_scores_cached", "sparse_attn", "dense_attn", "find_sinks", "select"):
+        for stage in ("block_means", "block_partials", "block_scores_cached", "sparse_attn", "dense_attn", "find_sinks", "probe_layer",
+                      "select"):
             st.issue(stage)
             sync()
         print(json.dumps({"mode": "pmc", "copy_bytes": int(src.numel() * 4), "workload": w.name}))
@@ -240,6 +241,8 @@ def main() -> int:
         "block_scores_cached": {"bytes": n_b * H * d * 4 + w.k_focus * H * d * 2 + n_b * 4, "flops": 2 * n_b * d * H},
         "sparse_attn": {"bytes": 2 * mean_keys * H * d * 2 + 2 * n_q * H * d * 2, "flops": 4 * n_q * mean_keys * d * H},
         "dense_attn": {"bytes": 2 * L * H * d * 2 + 2 * n_q * H * d * 2, "flops": 4 * n_q * L * d * H},
+        # the probe layer's own dense attention with the sinks as a by-product: K and V once
+        "probe_layer": {"bytes": 2 * L * H * d * 2 + 2 * n_q * H * d * 2 + L * 4, "flops": 4 * n_q * L * d * H},
     }
     # scoring from raw K: the scan emits the per-head partial relevances directly (no means are stored), then Top-C
     alg["block_scores"] = {"bytes": alg["block_partials"]["bytes"] + n_b * H * 4 + n_b * 4, "flops": alg["block_partials"]["flops"]}
@@ -323,9 +326,9 @@ def main() -> int:
     stages = {}
     per_step_count = {"select": 1, "find_sinks": 1, "block_means": n_sparse, "block_partials": n_sparse, "block_scores_cached": n_sparse,
                       "block_scores": n_sparse, "sparse_attn": n_sparse, "dense_attn": n_sparse, "sparse_layer": n_sparse,
-                      "sparse_layer_cached": n_sparse}
+                      "sparse_layer_cached": n_sparse, "probe_layer": 0}
     for stage in ("select", "find_sinks", "block_means", "block_partials", "block_scores_cached", "block_scores", "sparse_attn", "dense_attn",
-                  "sparse_layer_cached", "sparse_layer"):
+                  "sparse_layer_cached", "sparse_layer", "probe_layer"):
         us = time_stage(stage)
         a = alg[stage]
         stages[stage] = {"us_per_launch": round(us, 3), "launches_per_step": per_step_count[stage],
@@ -339,7 +342,8 @@ def main() -> int:
     share = {s: stages[s]["us_per_launch"] * per_step_count[s] for s in in_step}
     dom_kernel = max(share, key=share.get)
     ds = stages[dom_kernel]
-    qtw = 1 if n_q <= 16 else (2 if n_q <= 32 else 4)   # query tiles per workgroup the launchers pick
+    cap_q = st0.max_active                              # the launchers plan for the capacity of the active list
+    qtw = 1 if cap_q <= 16 else (2 if cap_q <= 32 else 4)   # query tiles per workgroup they pick
     kernel_name = {"block_partials": f"block_means_kernel<{d}, true>",
                    "find_sinks": f"qk_logits_kernel<{d}, {qtw}, {0 if qtw == 1 else 1}> and the rest of the sink chain",
                    "sparse_attn": f"sparse_attn_kernel<{d}, {qtw}, 1>", "select": "select_queries_kernel"}[dom_kernel]

@@ -12,6 +12,7 @@
  *     focus_block_scores     per sparse layer                   -> R_b, B_relevant
  *     focus_sparse_attn      per sparse layer                   -> Attn
  *     focus_sparse_layer     = focus_block_scores + focus_sparse_attn of one layer, fused into fewer launches
+ *     focus_probe_layer      = dense attention of the probe layer + focus_find_sinks, sharing the QK^T work
  *
  * Conventions shared by every entry point
  *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
@@ -67,7 +68,8 @@ typedef enum focus_fn {
   FOCUS_FN_BLOCK_SCORES = 1,
   FOCUS_FN_FIND_SINKS = 2,
   FOCUS_FN_SPARSE_ATTN = 3,
-  FOCUS_FN_SPARSE_LAYER = 4
+  FOCUS_FN_SPARSE_LAYER = 4,
+  FOCUS_FN_PROBE_LAYER = 5
 } focus_fn;
 
 /*
@@ -172,6 +174,20 @@ int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* a
                        const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink,
                        float* scores, int32_t* kept_blocks, void* out, float* lse, void* workspace, size_t ws_bytes,
                        void* stream);
+
+/*
+ * The probe layer in one call: a dense layer of Alg. 1 (l <= l_dense: every key is attended, queries restricted to
+ * I_active) whose attention also yields the sinks (Sec. 5.3: the attention of the last dense layer is the probe).
+ *   out, lse     what focus_sparse_attn returns with every block kept and no sinks (the key axis is cut into 32-row
+ *                tiles without regard to block boundaries, so bit-identical when M and B are multiples of 32)
+ *   col_mass, sink_idx   S_j and I_sink of Eq. 6 as in focus_find_sinks; col_mass may be NULL
+ * With at most 16 active queries the QK^T products of the attention are kept and reused, so K is read once for both
+ * results; with more, one extra pass over K turns the attention's row log-sum-exps into column sums.  The column
+ * masses agree with focus_find_sinks to rounding (the log-sum-exps are merged in a different order).
+ */
+int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active,
+                      const void* K, const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse,
+                      float* col_mass, int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream);
 
 /* Bytes of workspace `fn` needs for this shape; 0 on invalid arguments.  [host] only. */
 size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep,

@@ -16,10 +16,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocus_hip.so")
 
 FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0, -1, -2, -3, -4
-FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER = 1, 2, 3, 4
+FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER = 1, 2, 3, 4, 5
 
 EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
-           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
+           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
 
@@ -56,10 +56,12 @@ def lib() -> C.CDLL:
         L.focus_find_sinks.argtypes = [p, p, p, i32, p, sp, i32, p, p, p, sz, p]
         L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
+        L.focus_probe_layer.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, p, p, sz, p]
         L.focus_block_partials.argtypes = [p, p, p, i32, p, p, sp, p, p]
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
-                     "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks"):
+                     "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
+                     "focus_probe_layer"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
         L.focus_workspace_bytes.restype = sz
@@ -179,6 +181,17 @@ def sparse_attn(q, active_idx, counts, k, v, shape: Shape, kept_blocks, n_keep: 
     _need(out, torch.bfloat16, "out")
     _check(lib().focus_sparse_attn(_ptr(q), _ptr(active_idx), _ptr(counts), active_idx.numel(), _ptr(k), _ptr(v),
                                    C.byref(shape), _ptr(kept_blocks), n_keep, _ptr(sink_idx), n_sink, _ptr(out), _ptr(lse),
+                                   _ptr(workspace),
+                                   0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def probe_layer(q, active_idx, counts, k, v, shape: Shape, n_sink: int, out, lse, col_mass, sink_idx, workspace) -> None:
+    _need(q, torch.bfloat16, "Q")
+    _need(k, torch.bfloat16, "K")
+    _need(v, torch.bfloat16, "V")
+    _need(out, torch.bfloat16, "out")
+    _check(lib().focus_probe_layer(_ptr(q), _ptr(active_idx), _ptr(counts), active_idx.numel(), _ptr(k), _ptr(v),
+                                   C.byref(shape), n_sink, _ptr(out), _ptr(lse), _ptr(col_mass), _ptr(sink_idx),
                                    _ptr(workspace),
                                    0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
 

@@ -48,13 +48,10 @@ static void plan_splits(SplitPlan& p, int n_heads, int target_groups) {
   p.n_split = p.n_sub > 0 ? ceil_div(p.n_sub, per) : 1;
 }
 
-SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n_sink) {
-  SplitPlan p;
-  plan_queries(p, max_active);
-  p.n_sub = n_keep * ceil_div(s.block, kSubTile) + ceil_div(s.n_resp, kSubTile) + ceil_div(n_sink, kSubTile);
+static void plan_attention_splits(SplitPlan& p, const focus_shape& s) {
   plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS", 1024));
-  // Many sub-tiles per wavefront (dense comparison, alpha = 0.5) or several query tiles per workgroup (window-expanded
-  // queries): fewer, longer workgroups with double-buffered key loops.  One sub-tile per wavefront (the 3 % keep
+  // Many sub-tiles per wavefront (dense layers, alpha = 0.5) or several query tiles per workgroup (window-expanded
+  // queries): fewer, longer workgroups with pipelined key loops.  One sub-tile per wavefront (the 3 % keep
   // configurations): nothing to overlap.
   if (p.q_tiles_per_group > 1) {
     plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 512));  // two resident workgroups per compute unit
@@ -62,6 +59,21 @@ SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n
     plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 512));
     p.pipelined = p.per_split > kWavesPerGroup;
   }
+}
+
+SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n_sink) {
+  SplitPlan p;
+  plan_queries(p, max_active);
+  p.n_sub = n_keep * ceil_div(s.block, kSubTile) + ceil_div(s.n_resp, kSubTile) + ceil_div(n_sink, kSubTile);
+  plan_attention_splits(p, s);
+  return p;
+}
+
+SplitPlan plan_attention_dense(const focus_shape& s, int max_active) {
+  SplitPlan p;
+  plan_queries(p, max_active);
+  p.n_sub = ceil_div(s.n_ctx + s.n_resp, kSubTile);
+  plan_attention_splits(p, s);
   return p;
 }
 
@@ -132,6 +144,9 @@ static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
   return w;
 }
 
+struct ProbeWs {
+  size_t part_o, part_ml, lse2, scratch, col_mass, cand, total;  // scratch: logits [H, L, 16] or column sums [q_groups H, L]
+};
 struct AttnWs {
   size_t part_o, part_ml, total;
 };
@@ -141,6 +156,25 @@ static AttnWs ws_attn(const focus_shape& s, const SplitPlan& p) {
   size_t off = align_up((size_t)s.n_heads * p.q_pad * p.n_split * s.head_dim * sizeof(float));
   w.part_ml = off;
   off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+static ProbeWs ws_probe_layer(const focus_shape& s, const SplitPlan& pa) {
+  ProbeWs w;
+  const size_t L = (size_t)s.n_ctx + s.n_resp;
+  const AttnWs a = ws_attn(s, pa);
+  w.part_o = a.part_o;
+  w.part_ml = a.part_ml;
+  size_t off = a.total;
+  w.lse2 = off;
+  off += align_up((size_t)s.n_heads * pa.q_pad * sizeof(float));
+  w.scratch = off;
+  off += align_up(sinks_two_pass(pa) ? (size_t)pa.q_groups * s.n_heads * L * sizeof(float) : (size_t)s.n_heads * L * 16 * sizeof(float));
+  w.col_mass = off;
+  off += align_up(L * sizeof(float));
+  w.cand = off;
+  off += align_up((size_t)kTournamentMaxCand * sizeof(int32_t));
   w.total = off;
   return w;
 }
@@ -186,6 +220,9 @@ size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_a
           n_sink > shape->n_ctx)
         return 0;
       return ws_attn(*shape, plan_attention(*shape, max_active, n_keep, n_sink)).total;
+    case FOCUS_FN_PROBE_LAYER:
+      if (max_active < 1 || max_active > shape->n_gen) return 0;
+      return ws_probe_layer(*shape, plan_attention_dense(*shape, max_active)).total;
     case FOCUS_FN_SPARSE_LAYER:
       if (max_active < 1 || max_active > shape->n_gen || n_keep < 0 || n_keep > n_b || n_sink < 0 ||
           n_sink > shape->n_ctx)
@@ -324,6 +361,55 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   } else if (n_sink > 0) {
     e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N)", e);
+  }
+  return FOCUS_OK;
+}
+
+int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active, const void* K,
+                      const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse, float* col_mass,
+                      int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream) {
+  if (int rc = check_shape(shape, true, true, true, true)) return rc;
+  if (!Q || !active_idx || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_probe_layer: NULL pointer");
+  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "focus_probe_layer: max_active=%d not in [1, n_gen]", max_active);
+  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "focus_probe_layer: n_sink=%d not in [0, n_ctx]", n_sink);
+  if (n_sink > 0 && !sink_idx) return fail(FOCUS_EINVAL, "focus_probe_layer: sink_idx is NULL");
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out))
+    return fail(FOCUS_EINVAL, "focus_probe_layer: pointers must be 16-byte aligned");
+  const SplitPlan pa = plan_attention_dense(*shape, max_active);
+  const ProbeWs w = ws_probe_layer(*shape, pa);
+  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "focus_probe_layer: workspace needs %zu bytes, 16-byte aligned", w.total);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* lse2 = reinterpret_cast<float*>(ws + w.lse2);
+  float* scratch = reinterpret_cast<float*>(ws + w.scratch);
+  float* S = col_mass ? col_mass : reinterpret_cast<float*>(ws + w.col_mass);
+  const int L = shape->n_ctx + shape->n_resp;
+  const bool two_pass = sinks_two_pass(pa);
+  // dense attention of the active queries over all keys; with at most 16 queries its QK^T products are kept
+  DenseProbe probe;
+  probe.logits_out = two_pass ? nullptr : scratch;
+  probe.lse2_out = lse2;
+  hipError_t e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, nullptr, 0, nullptr, 0, pa, out, lse,
+                                    reinterpret_cast<float*>(ws + w.part_o), reinterpret_cast<float*>(ws + w.part_ml), nullptr,
+                                    st, &probe);
+  if (e != hipSuccess) return launch_fail("focus_probe_layer(attention)", e);
+  if (two_pass) {  // more queries: one more pass over K turns the known row log-sum-exps into column sums
+    const SplitPlan pl = plan_logits(*shape, max_active);
+    e = launch_qk_logits(Q, active_idx, counts, max_active, K, *shape, pl, 2, nullptr, nullptr, lse2, scratch, st);
+    if (e != hipSuccess) return launch_fail("focus_probe_layer(column sums)", e);
+  }
+  const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
+  int32_t* cand = tournament ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  e = launch_column_mass(scratch, two_pass, lse2, counts, max_active, two_pass ? pa.q_groups * shape->n_heads : shape->n_heads,
+                         shape->n_heads, L, S, shape->n_ctx, n_sink, cand, st);
+  if (e != hipSuccess) return launch_fail("focus_probe_layer(column mass)", e);
+  if (tournament) {
+    e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N, tournament)", e);
+  } else if (n_sink > 0) {
+    e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N)", e);
   }
   return FOCUS_OK;
 }

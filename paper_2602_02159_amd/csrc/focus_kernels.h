@@ -27,6 +27,7 @@ struct SplitPlan {
 };
 
 SplitPlan plan_attention(const focus_shape& s, int max_active, int n_keep, int n_sink);
+SplitPlan plan_attention_dense(const focus_shape& s, int max_active);  // all M + N rows, no block structure
 SplitPlan plan_logits(const focus_shape& s, int max_active);
 
 // ---- small kernels (focus_small.hip)
@@ -72,9 +73,17 @@ struct FusedTopC {
   int32_t* kept_out;      // [n_keep]
   int n_focus_max;
 };
+// Dense (probe) layer: every one of the M + N key rows is attended (kept_blocks / sink_idx unused, plan from
+// plan_attention_dense); optionally the scaled logits (at most 16 active queries) and the base-2 row log-sum-exps are
+// written for the sink scoring that follows.
+struct DenseProbe {
+  float* logits_out;  // [H, M + N, 16] or null
+  float* lse2_out;    // [H, q_pad] or null
+};
 hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                               const void* K, const void* V, const focus_shape& s, const int32_t* kept_blocks,
                               int n_keep, const int32_t* sink_idx, int n_sink, const SplitPlan& p, void* out,
-                              float* lse, float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st);
+                              float* lse, float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st,
+                              const DenseProbe* probe = nullptr);
 
 }  // namespace focus

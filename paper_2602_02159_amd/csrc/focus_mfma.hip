@@ -81,7 +81,8 @@ __device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xfffffff
 // Locate sub-tile `st` of the attention key list: kept blocks first (n_keep * sub_per_block sub-tiles), then
 // the response rows, then the sinks.  Block ids outside [0, n_b) are skipped.  The union of Eq. 8 is a set:
 // a sink is dropped when it is outside the prompt, inside a kept block or listed earlier in sink_idx (the block
-// list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r.
+// list itself must not repeat a block).  For sink sub-tiles lane r < 32 owns slot r.  dense_rows > 0 replaces all of
+// that by "all of the first dense_rows rows".
 //   "inside a kept block": one look-up in `kept_bits` (bit b set <=> block b is kept; LDS, built by the workgroup)
 //   when that is given, else the block list is scanned 64 entries per load.
 //   "listed earlier": a strictly ascending list (what focus_find_sinks writes) cannot repeat an entry; `ascending`
@@ -91,11 +92,17 @@ constexpr int kBitmapBlocks = 8192;  // largest n_b for which workgroups keep a 
 __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
                                                   const int32_t* __restrict__ kept_blocks, int n_keep,
                                                   const int32_t* __restrict__ sink_idx, int n_sink,
-                                                  const uint32_t* kept_bits = nullptr, int ascending = -1) {
+                                                  const uint32_t* kept_bits = nullptr, int ascending = -1,
+                                                  int dense_rows = 0) {
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
+  if (dense_rows > 0) {  // every key row takes part (dense layers): sub-tile st is rows [32 st, 32 st + 32)
+    t.row0 = st * kSubTile;
+    t.vmask = low_mask(min(dense_rows - t.row0, kSubTile));
+    return t;
+  }
   const int n_blk_sub = n_keep * sub_per_block;
   const int n_resp_sub = (N + kSubTile - 1) / kSubTile;
   if (st < n_blk_sub) {
@@ -402,6 +409,10 @@ struct AttnArgs {
   float* scores_out;      // [n_b] or null
   int32_t* kept_out;      // [n_keep]
   int n_focus_max;
+  // dense (probe) layer only
+  int dense_rows;     // > 0: attend to all of the first dense_rows = M + N key rows, block and sink lists unused
+  float* logits_out;  // [H, L, 16] scaled base-2 logits of the (at most 16) active queries, or null
+  float* lse2_out;    // [H, q_pad] base-2 log-sum-exp per row (+inf for an empty row), or null
 };
 
 // Merge of per-split partial results for one (head, active row a): out = sum_s f_s O_s / sum_s f_s l_s with
@@ -409,7 +420,8 @@ struct AttnArgs {
 template <int D>
 __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, const float* __restrict__ part_ml, int h, int a,
                                              int mc, int q_pad, int n_split, int max_active, uint16_t* __restrict__ out,
-                                             int64_t osh, int64_t osn, float* __restrict__ lse, bool write_lse) {
+                                             int64_t osh, int64_t osn, float* __restrict__ lse, float* __restrict__ lse2,
+                                             bool write_lse) {
   constexpr int kPerThread = D / 16;
   constexpr int kVec = kPerThread / 4;
   constexpr int kBatch = 8;
@@ -455,6 +467,7 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
     *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
   if (lse && write_lse)
     lse[(int64_t)h * max_active + a] = lsum > 0.f ? (mrun + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+  if (lse2 && write_lse) lse2[(int64_t)h * q_pad + a] = lsum > 0.f ? mrun + __builtin_amdgcn_logf(lsum) : INFINITY;
 }
 
 // One workgroup works on one (head, key split, group of QT query tiles); the key axis is walked in rounds of four
@@ -475,6 +488,8 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
 // FUSE bit 0 clear: kept_blocks comes from memory.
 // FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
 // them itself — every workgroup repeats this small computation instead of waiting for a separate Top-C kernel.
+// FUSE bit 2 set (QT = 1, dense probe layer): the scaled logits of every (query, key) are also written out, so that
+// the column attention mass of Eq. 6 needs no QK^T pass of its own.
 // FUSE bit 1 set (QT = 1 only): double-buffered key loop for launches in which a wavefront walks several sub-tiles
 // (the dense comparison): the next sub-tile's rows are requested into registers while the current one is
 // multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
@@ -487,6 +502,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   constexpr bool FUSED = (FUSE & 1) != 0;                // Top-C in the prologue
   constexpr bool SHARED = QT > 1;                        // staged sub-tiles are shared by the wavefronts
   constexpr bool PIPE = (FUSE & 2) != 0;                 // QT = 1 only: two K/V stages per wavefront
+  constexpr bool SPILL = (FUSE & 4) != 0;                // QT = 1, dense: also write the scaled logits (sink scoring)
+  static_assert(!SPILL || QT == 1, "logits are spilled for one query tile only");
   static_assert(!(PIPE && SHARED), "shared sub-tiles have their own pipelining");
   constexpr int W = QT == 4 ? 2 * kWavesPerGroup : kWavesPerGroup;  // wavefronts in the workgroup
   constexpr int KG = W / QT;                             // wavefronts per query tile, each on its own slots
@@ -552,7 +569,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   {
     const int first_sink_sub = p.n_keep * p.sub_per_block + (p.N + kSubTile - 1) / kSubTile;
     const int my_end = min((int)(blockIdx.x + 1) * p.per_split, p.n_sub);
-    if (p.n_sink > 0 && my_end > first_sink_sub) {  // uniform over the workgroup
+    if (p.dense_rows == 0 && p.n_sink > 0 && my_end > first_sink_sub) {  // uniform over the workgroup
       const bool bitmap = p.n_keep > 0 && p.n_b <= kBitmapBlocks;
       const int words = bitmap ? (p.n_b + 31) >> 5 : 0;
       for (int i = threadIdx.x; i < words; i += blockDim.x) kept_bits_sh[i] = 0u;
@@ -595,7 +612,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     const int sub = st_begin + 2 * ph + h_i;
     if (sub < st_end)
       tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending);
+                          sinks_ascending, p.dense_rows);
     if (tp.vmask != 0u)
       fetch_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink, lane, h_first, rh);
     return tp;
@@ -610,7 +627,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   if (SHARED) t_half = fetch_half(0);
   if (!SHARED && st < st_end) {
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending);
+                          sinks_ascending, p.dense_rows);
     if (t.vmask != 0u) {
       if (PIPE) {
         fetch_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, lane, rk);
@@ -633,11 +650,19 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   bool first = true;
-  auto consume = [&](const char* sK, const char* sV, uint32_t vmask) {  // one staged sub-tile into the running softmax
+  auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) {  // one staged sub-tile into the running softmax
     FOCUS_STAMP(3);
     floatx4 acc[1][2];
     qk_subtile<D, 1>(acc, sK, q, lane);
     FOCUS_STAMP(4);
+    if (SPILL) {  // contiguous rows only (dense): key row = row0 + slot
+      float* dst = p.logits_out + ((int64_t)h * p.dense_rows + row0) * 16 + c;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
+        if ((vmask >> slot) & 1u) dst[slot * 16] = acc[0][e >> 2][e & 3] * p.scale_log2;
+      }
+    }
     float ps[8];
     const float alpha = softmax_step(acc[0], vmask, g, p.scale_log2, m_run, l_run, ps);
     // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
@@ -665,7 +690,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   };
   auto locate = [&](int sub) {
     return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending);
+                          sinks_ascending, p.dense_rows);
   };
   if (PIPE && t.vmask != 0u) {  // the first sub-tile: registers -> this wavefront's slot of buffer A
     store_subtile<D>(stageK, lane, rk);
@@ -686,7 +711,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[sl]);
       if (vm != 0u) {
         const char* cK = ldsA + sl * kBufBytes;
-        consume(cK, cK + G::kStageBytes, vm);
+        consume(cK, cK + G::kStageBytes, vm, 0);
       }
       if (ph + 1 < n_half) {  // the rows requested a whole half round ago go into the slots freed by half round ph - 1,
         store_half(ph + 1, tn);  // and the registers take the request after next straight away
@@ -699,7 +724,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       const uint32_t vmask = t.vmask;
       if (vmask != 0u) {
         wait_loads();
-        consume(stageK, stageV, vmask);
+        consume(stageK, stageV, vmask, t.row0);
       }
       st += kWavesPerGroup;
       if (st < st_end) {
@@ -721,7 +746,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
         fetch_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, lane, rk);
         fetch_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, lane, rv);
       }
-      if (t.vmask != 0u) consume(cur, cur + G::kStageBytes, t.vmask);
+      if (t.vmask != 0u) consume(cur, cur + G::kStageBytes, t.vmask, t.row0);
       if (tn.vmask != 0u) {
         store_subtile<D>(nxt, lane, rk);
         store_subtile<D>(nxt + G::kStageBytes, lane, rv);
@@ -793,6 +818,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
           *reinterpret_cast<uint32_t*>(dst + i) = cvt_pk_bf16(acc_o[i] * inv, acc_o[i + 1] * inv);
         if (p.lse && (threadIdx.x & 15) == 0)
           p.lse[(int64_t)h * p.max_active + a] = lsum > 0.f ? (mmax + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+        if (p.lse2_out && (threadIdx.x & 15) == 0)
+          p.lse2_out[(int64_t)h * p.q_pad + a] = lsum > 0.f ? mmax + __builtin_amdgcn_logf(lsum) : INFINITY;
       } else {
         const int64_t row = ((int64_t)h * p.q_pad + a) * p.n_split + split;
         float* dst = p.part_o + row * D + mc;
@@ -815,13 +842,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
                                                            const float* __restrict__ part_ml,
                                                            const int32_t* __restrict__ counts, int max_active, int q_pad,
                                                            int n_split, uint16_t* __restrict__ out, int64_t osh, int64_t osn,
-                                                           float* __restrict__ lse) {
+                                                           float* __restrict__ lse, float* __restrict__ lse2) {
   const int h = blockIdx.y;
   const int a = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int mc = (threadIdx.x & 15) * (D / 16);
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
   if (a >= n_act) return;
-  merge_splits<D>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, out, osh, osn, lse, (threadIdx.x & 15) == 0);
+  merge_splits<D>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, out, osh, osn, lse, lse2, (threadIdx.x & 15) == 0);
 }
 
 template <int D, int QT>
@@ -829,7 +856,13 @@ static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fuse
   dim3 grid(p.n_split, a.H, p.q_groups);
   const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) have their own pipelining
   const dim3 block(QT == 4 ? 512 : 256);
-  if (fused && pipe)
+  if (a.logits_out != nullptr) {  // dense probe layer with the logits spilled; QT == 1 by construction
+    if (QT != 1 || fused) return hipErrorInvalidValue;
+    if (pipe)
+      hipLaunchKernelGGL((sparse_attn_kernel<D, 1, 6>), grid, block, 0, st, a);
+    else
+      hipLaunchKernelGGL((sparse_attn_kernel<D, 1, 4>), grid, block, 0, st, a);
+  } else if (fused && pipe)
     hipLaunchKernelGGL((sparse_attn_kernel<D, QT, (QT == 1 ? 3 : 1)>), grid, block, 0, st, a);
   else if (fused)
     hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 1>), grid, block, 0, st, a);
@@ -840,15 +873,19 @@ static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fuse
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
-                     a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse);
+                     a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
   return hipGetLastError();
 }
 
 hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                               const void* K, const void* V, const focus_shape& s, const int32_t* kept_blocks, int n_keep,
                               const int32_t* sink_idx, int n_sink, const SplitPlan& p, void* out, float* lse,
-                              float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st) {
+                              float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st,
+                              const DenseProbe* probe) {
   AttnArgs a;
+  a.dense_rows = probe ? s.n_ctx + s.n_resp : 0;
+  a.logits_out = probe ? probe->logits_out : nullptr;
+  a.lse2_out = probe ? probe->lse2_out : nullptr;
   a.Q = static_cast<const uint16_t*>(Q);
   a.K = static_cast<const uint16_t*>(K);
   a.V = static_cast<const uint16_t*>(V);

@@ -19,7 +19,8 @@ class FocusStep:
     """Buffers and call sequence for one step.
 
     Layers are (q, k, v) bf16 CUDA tensors in [H, rows, d] layout: q [H, n_gen, d]; k, v [H, M+N, d].
-    `probe` is the (q, k) pair of the layer whose attention identifies the sinks.
+    `probe` is the (q, k) pair of the layer whose attention identifies the sinks, or its (q, k, v) triple: then the
+    stage "probe_layer" (that layer's dense attention and the sinks in one call) is available as well.
     """
 
     def __init__(self, conf, masked, probe, sparse_layers, n_ctx: int, block: int, k_focus: int, window: int, n_keep: int,
@@ -62,8 +63,16 @@ class FocusStep:
                                                  C.byref(s_probe), n_sink, p(self.col_mass), p(self.sink_idx), p(ws_sinks),
                                                  ws_sinks.numel()))],
             "block_means": [], "block_scores": [], "block_scores_cached": [], "sparse_attn": [], "dense_attn": [],
-            "sparse_layer": [], "sparse_layer_cached": [], "block_partials": [],
+            "sparse_layer": [], "sparse_layer_cached": [], "block_partials": [], "probe_layer": [],
         }
+        if len(probe) == 3:
+            self.probe_out = torch.zeros((self.H, self.max_active, self.d), dtype=torch.bfloat16, device=dev)
+            s_pl = fb.make_shape(probe[0], probe[1], probe[2], n_ctx, block, self.probe_out)
+            self._keep.append(s_pl)
+            ws_pl = workspace(fb.workspace_bytes(fb.FN_PROBE_LAYER, s_pl, self.max_active))
+            self.calls["probe_layer"] = [(L.focus_probe_layer, (
+                p(probe[0]), p(self.active_idx), p(self.counts), self.max_active, p(probe[1]), p(probe[2]), C.byref(s_pl),
+                n_sink, p(self.probe_out), None, p(self.col_mass), p(self.sink_idx), p(ws_pl), ws_pl.numel()))]
         ws_scores = ws_attn = ws_dense = ws_layer = None
         for (q, k, v), b in zip(self.layers, self.bufs):
             s = fb.make_shape(q, k, v, n_ctx, block, b["out"])

@@ -116,3 +116,19 @@ def gpu_sparse_layer(q, focus, active, counts, k, v, kbar, n_ctx, block, n_keep,
     fb.sparse_layer(q, focus, active, counts, k, v, kbar, s, n_keep, sinks if n_sink else None, n_sink, scores, kept, out, lse, w)
     torch.cuda.synchronize()
     return scores, kept[:n_keep], out, lse
+
+
+def gpu_probe_layer(q, active, counts, k, v, n_ctx, block, n_sink):
+    H, _, d = q.shape
+    L = k.shape[1]
+    max_active = active.numel()
+    out = torch.full((H, max_active, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((H, max_active), float("nan"), dtype=torch.float32, device=DEV)
+    col = torch.full((L,), float("nan"), dtype=torch.float32, device=DEV)
+    sinks = i32(None, max(n_sink, 1))
+    s = fb.make_shape(q, k, v, n_ctx, block, out)
+    w = ws(fb.workspace_bytes(fb.FN_PROBE_LAYER, s, max_active))
+    w.fill_(0xCD)
+    fb.probe_layer(q, active, counts, k, v, s, n_sink, out, lse, col, sinks, w)
+    torch.cuda.synchronize()
+    return out, lse, col, sinks[:n_sink]

@@ -316,6 +316,44 @@ def test_sparse_attn_many_sinks_inside_and_outside_kept_blocks(G, n_act, ascendi
     assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
 
 
+# ------------------------------------------------------------------------------------------------ probe layer
+@pytest.mark.parametrize("H,M,N,d,B,n_gen,n_act,n_sink", [
+    (4, 1024, 32, 64, 64, 32, 8, 2),          # the tiny shape: a single key split
+    (3, 2050, 33, 128, 128, 80, 16, 4),       # 16 queries: logits kept from the attention pass
+    (2, 8192, 64, 128, 128, 64, 16, 20),      # several splits, radix Top-N
+    (2, 4100, 30, 128, 64, 64, 28, 7),        # two query tiles: column sums from a second pass over K
+    (2, 3000, 0, 64, 64, 96, 72, 41),         # five query tiles (two groups), d = 64, no response rows
+])
+def test_probe_layer(G, H, M, N, d, B, n_gen, n_act, n_sink):
+    """Dense attention of the active queries over every key plus the sinks it implies, in one call: the attention equals
+    focus_sparse_attn with every block kept (bit for bit when the tiles coincide), the column masses and sinks match
+    the oracle (and focus_find_sinks to rounding)."""
+    q, k, v = (_rand_bf16(81 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    act = np.sort(np.random.default_rng(84).choice(n_gen, n_act, replace=False))
+    cap = n_act + 2
+    active, counts = G.i32(list(act) + [-1] * (cap - n_act)), G.i32([0, n_act])
+    out, lse, col, sinks = G.gpu_probe_layer(q, active, counts, k, v, M, B, n_sink)
+    n_b = -(-M // B)
+    out_d, lse_d = G.gpu_sparse_attn(q, active, counts, k, v, M, B, G.i32(np.arange(n_b)), None)
+    if M % 32 == 0 and B % 32 == 0:    # the 32-row tiles of both paths coincide: same arithmetic in the same order
+        assert torch.equal(out[:, :n_act], out_d[:, :n_act]) and torch.equal(lse[:, :n_act], lse_d[:, :n_act])
+    else:                              # the dense path tiles the key axis without regard to block boundaries
+        assert np.allclose(G.to_np(out[:, :n_act]), G.to_np(out_d[:, :n_act]), atol=2e-3)
+        assert np.allclose(lse[:, :n_act].cpu().numpy(), lse_d[:, :n_act].cpu().numpy(), atol=1e-5)
+    Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
+    ref, ref_lse = fo.sparse_attention(Q, act, K, V, np.arange(M), M)
+    G.assert_attention_close(out[:, :n_act], ref)
+    assert np.allclose(lse[:, :n_act].cpu().numpy(), ref_lse, atol=2e-3)
+    Sref = fo.sink_scores(Q, act, K)
+    S = col.cpu().numpy().astype(np.float64)
+    assert np.allclose(S, Sref, rtol=2e-4, atol=1e-9) and S.sum() == pytest.approx(1.0, abs=1e-4)
+    assert fo.decision_margin(Sref, n_sink, np.arange(M + N) < M) > 1e-5, "test inputs produce a near-tie; pick another seed"
+    assert sinks.cpu().tolist() == fo.select_sinks(Sref, M, n_sink).tolist()
+    assert sinks.cpu().tolist() == fo.select_sinks(S, M, n_sink).tolist()
+    col2, sinks2 = G.gpu_find_sinks(q, active, counts, k, M, B, n_sink)
+    assert np.allclose(col2.cpu().numpy(), S, rtol=1e-5, atol=1e-12) and torch.equal(sinks, sinks2)
+
+
 # ------------------------------------------------------------------------------------------------ fused layer call
 @pytest.mark.parametrize("H,M,N,d,B,n_gen,n_f,n_act,n_keep,n_sink", [
     (4, 1024, 32, 64, 64, 32, 8, 8, 4, 2),

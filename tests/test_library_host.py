@@ -52,6 +52,7 @@ def test_workspace_sizes(L):
     assert fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, 8, 4, 2) > 0
     assert fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, 8, 17, 2) == 0      # n_keep > n_b
     assert fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, 33, 4, 2) == 0      # more active rows than Q has
+    assert fb.workspace_bytes(fb.FN_PROBE_LAYER, s, 8) >= 4 * 1056 * 16 * 4
     assert fb.workspace_bytes(99, s) == 0
     assert fb.workspace_bytes(fb.FN_FIND_SINKS, _shape(head_dim=96), 8) == 0
 
@@ -87,6 +88,10 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 17, fake, fake, None) == fb.FOCUS_EINVAL
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, None, fake, None) == fb.FOCUS_EINVAL
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, fake, None, None) == fb.FOCUS_EINVAL
+    # probe layer: NULL V, n_sink out of range, workspace too small
+    assert L.focus_probe_layer(fake, fake, None, 8, fake, None, sp, 2, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_probe_layer(fake, fake, None, 8, fake, fake, sp, 5000, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_probe_layer(fake, fake, None, 8, fake, fake, sp, 2, fake, None, None, fake, fake, 4096, None) == fb.FOCUS_EWORKSPACE
     # find sinks: n_sink out of range, workspace too small
     assert L.focus_find_sinks(fake, fake, None, 8, fake, sp, 2000, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_find_sinks(fake, fake, None, 8, fake, sp, 2, None, fake, fake, 1024, None) == fb.FOCUS_EWORKSPACE
