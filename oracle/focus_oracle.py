@@ -21,7 +21,8 @@ Readings taken where the paper leaves a choice (each restated where it is used):
     query) over all L keys, then the mean over heads and active queries; only prompt
     positions are sink candidates;
   * the last prompt block may be shorter than B and is averaged over its true length;
-  * the key set of the sparse attention is a set: a sink inside a kept block counts once.
+  * the key set of the sparse attention is a set: a sink inside a kept block counts once;
+  * the arg max of Eq. 2 goes to the lower token id when several tokens share the maximum.
 
 Pins (tests/test_oracle_*.py): dense reduction against an independent attention, softmax row
 sums, brute-force top-k, closed forms (equal keys, single key, one-hot), linearity of the
@@ -38,7 +39,7 @@ import numpy as np
 __all__ = [
     "widen_bf16", "top_indices", "decision_margin", "select_focus", "expand_window", "block_means",
     "block_relevance", "select_blocks", "sink_scores", "select_sinks", "attention_index_set",
-    "sparse_attention", "focus_layer", "focus_step",
+    "sparse_attention", "focus_layer", "focus_step", "token_confidence", "cache_update",
 ]
 
 
@@ -229,3 +230,41 @@ def focus_step(conf, masked, k: int, w: int, lo: int, hi: int, layers, probe_lay
         per_layer[l] = focus_layer(Q, K, V, focus, active, sinks, n_ctx, block, n_keep)
         per_layer[l]["sinks_used"] = sinks  # the identical object on purpose
     return {"focus": focus, "active": active, "S": S, "sinks": sinks, "layers": per_layer}
+
+
+# ----------------------------------------------------------------------------- around the step (Sec. 3)
+def token_confidence(logits, masked=None):
+    """Predicted token and confidence of every position (Eq. 2).
+
+    p(x_i = v) is the softmax of row i of `logits` [n, |V|] over the vocabulary;
+    x_hat_i = argmax_v p(x_i = v) and c_i = max_v p(x_i = v) = 1 / sum_v exp(logit_iv - max_v logit_iv).
+    The paper does not say which token wins a tie of the maximum: the lower id does.  Positions with
+    masked[i] == 0 are no candidates of Eq. 4; they get token -1 and confidence 0.
+    Returns (tokens int64 [n], conf float64 [n]).
+    """
+    x = _f64(logits)
+    n, _ = x.shape
+    tokens = np.full(n, -1, dtype=np.int64)
+    conf = np.zeros(n, dtype=np.float64)
+    for i in range(n):
+        if masked is not None and not masked[i]:
+            continue
+        row = x[i]
+        m = row.max()
+        tokens[i] = int(np.flatnonzero(row == m)[0])
+        conf[i] = 1.0 / np.exp(row - m).sum()
+    return tokens, conf
+
+
+def cache_update(K_cache, V_cache, K_new, V_new, active, row_base: int):
+    """Approximate KV cache (Eq. 3): the refreshed set U = {row_base + i : i in I_active} takes the newly
+    computed states, every other row keeps its cached one.
+
+    K_cache, V_cache [H, L, d]; K_new, V_new [H, >= |I_active|, d] hold the new states of the active positions in
+    list order; `row_base` is the cache row of position 0 of the generation block.  Returns new arrays.
+    """
+    K_out, V_out = np.array(K_cache, copy=True), np.array(V_cache, copy=True)
+    for a, i in enumerate(np.asarray(active, dtype=np.int64).tolist()):
+        K_out[:, row_base + i, :] = K_new[:, a, :]
+        V_out[:, row_base + i, :] = V_new[:, a, :]
+    return K_out, V_out

@@ -147,3 +147,30 @@ def test_recomputing_sinks_per_layer_is_caught(monkeypatch):
             lay["sinks_used"] = r["sinks"].copy()     # equal values, but not the array handed down
         return r
     assert _pins_reject(monkeypatch, "focus_step", broken, [pins.test_step_reuses_probe_layer_sinks_unchanged])
+
+
+@pytest.mark.parametrize("variant", ["max_logit", "tie_high", "ignore_mask"])
+def test_wrong_token_confidence_is_caught(monkeypatch, variant):
+    def broken(logits, masked=None):
+        x = _f64(logits)
+        tok, conf = np.full(len(x), -1, dtype=np.int64), np.zeros(len(x))
+        for i, row in enumerate(x):
+            if variant != "ignore_mask" and masked is not None and not masked[i]:
+                continue
+            m = row.max()
+            hits = np.flatnonzero(row == m)
+            tok[i] = int(hits[-1] if variant == "tie_high" else hits[0])
+            conf[i] = m if variant == "max_logit" else 1.0 / np.exp(row - m).sum()     # the logit instead of the probability
+        return tok, conf
+    assert _pins_reject(monkeypatch, "token_confidence", broken,
+                        [pins.test_token_confidence_closed_forms, pins.test_token_confidence_invariances_and_mask])
+
+
+def test_cache_update_at_the_wrong_rows_is_caught(monkeypatch):
+    def broken(K_cache, V_cache, K_new, V_new, active, row_base):
+        K_out, V_out = np.array(K_cache, copy=True), np.array(V_cache, copy=True)
+        for a, i in enumerate(active):
+            K_out[:, i, :] = K_new[:, a, :]        # block-relative position used as a cache row
+            V_out[:, i, :] = V_new[:, a, :]
+        return K_out, V_out
+    assert _pins_reject(monkeypatch, "cache_update", broken, [pins.test_cache_update_touches_exactly_the_refreshed_rows])

@@ -317,3 +317,71 @@ def test_widen_bf16_exact():
     t = torch.tensor([1.0, -2.5, 0.333, 1e-30, 3e38, 0.0, -0.0], dtype=torch.bfloat16)
     bits = t.view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(fo.widen_bf16(bits), t.to(torch.float64).numpy())
+
+
+# ----------------------------------------------------------------------------- Eq. 2 and Eq. 3
+def test_token_confidence_against_torch_softmax_and_brute_force():
+    rng = np.random.default_rng(71)
+    x = rng.normal(0, 3, (6, 257))
+    tok, conf = fo.token_confidence(x)
+    p = torch.softmax(torch.from_numpy(x), dim=1)
+    assert np.allclose(conf, p.max(dim=1).values.numpy(), rtol=1e-12)
+    assert tok.tolist() == p.argmax(dim=1).tolist()            # no ties in continuous random data
+    for i in range(6):                                          # and written out term by term
+        z = [math.exp(v) for v in x[i]]
+        assert conf[i] == pytest.approx(max(z) / sum(z), rel=1e-12)
+
+
+def test_token_confidence_closed_forms():
+    V = 1000
+    tok, conf = fo.token_confidence(np.zeros((1, V)))
+    assert tok.tolist() == [0] and conf[0] == pytest.approx(1.0 / V, rel=1e-14)       # uniform: 1/|V|, lowest id wins
+    x = np.full((1, V), -3.0)
+    x[0, [17, 400]] = 2.0                                                              # two equal maxima
+    tok, conf = fo.token_confidence(x)
+    assert tok.tolist() == [17]
+    assert conf[0] == pytest.approx(1.0 / (2.0 + (V - 2) * math.exp(-5.0)), rel=1e-13)
+    x = np.zeros((1, V))
+    x[0, 123] = 80.0                                                                   # one dominant token
+    tok, conf = fo.token_confidence(x)
+    assert tok.tolist() == [123] and conf[0] == pytest.approx(1.0, abs=1e-30)
+    x[0, 5] = -np.inf                                                                  # an excluded token changes nothing else
+    assert fo.token_confidence(x)[1][0] == pytest.approx(1.0, abs=1e-30)
+
+
+def test_token_confidence_invariances_and_mask():
+    rng = np.random.default_rng(72)
+    x = rng.normal(0, 2, (5, 300))
+    tok, conf = fo.token_confidence(x)
+    tok2, conf2 = fo.token_confidence(x + 11.5)                 # softmax ignores a common shift
+    assert tok.tolist() == tok2.tolist() and np.allclose(conf, conf2, rtol=1e-12)
+    perm = rng.permutation(300)
+    tok3, conf3 = fo.token_confidence(x[:, perm])               # relabelling the vocabulary relabels the token
+    assert np.allclose(conf, conf3, rtol=1e-12) and [int(perm[t]) for t in tok3] == tok.tolist()
+    assert ((conf > 1.0 / 300) & (conf <= 1.0)).all()
+    masked = np.array([1, 0, 1, 0, 0], dtype=np.uint8)
+    tok4, conf4 = fo.token_confidence(x, masked)
+    assert tok4.tolist() == [tok[0], -1, tok[2], -1, -1] and conf4.tolist() == [conf[0], 0.0, conf[2], 0.0, 0.0]
+    # the confidences feed Eq. 4 directly
+    assert fo.select_focus(conf4, masked, 1).tolist() == [0 if conf[0] >= conf[2] else 2]
+
+
+def test_cache_update_touches_exactly_the_refreshed_rows():
+    rng = np.random.default_rng(73)
+    H, L, d, base = 3, 40, 8, 25
+    Kc, Vc = rng.normal(size=(H, L, d)), rng.normal(size=(H, L, d))
+    active = [1, 4, 5, 12]
+    Kn, Vn = rng.normal(size=(H, 6, d)), rng.normal(size=(H, 6, d))      # two spare slots past the active list
+    K2, V2 = fo.cache_update(Kc, Vc, Kn, Vn, active, base)
+    for h in range(H):
+        for r in range(L):
+            if r - base in active:
+                a = active.index(r - base)
+                assert (K2[h, r] == Kn[h, a]).all() and (V2[h, r] == Vn[h, a]).all()
+            else:
+                assert (K2[h, r] == Kc[h, r]).all() and (V2[h, r] == Vc[h, r]).all()
+    assert (Kc != K2).any() and K2 is not Kc                           # a copy; the inputs are untouched
+    K3, V3 = fo.cache_update(K2, V2, Kn, Vn, active, base)             # idempotent
+    assert (K3 == K2).all() and (V3 == V2).all()
+    K4, _ = fo.cache_update(Kc, Vc, Kn, Vn, [], base)                  # U empty: pure reuse
+    assert (K4 == Kc).all()
