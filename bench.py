@@ -336,6 +336,51 @@ def main() -> int:
                          "GBps": round(a["bytes"] / us * 1e-3, 1), "TFLOPps": round(a["flops"] / us * 1e-6, 3),
                          "hbm_frac": round(a["bytes"] / us * 1e-3 / HBM_PEAK_GBS, 4)}
 
+    # ---- the two operations around the step (not part of `value`): confidence from vocabulary logits (Eq. 2) for the
+    # generation block, and the KV-cache refresh of the active rows (Eq. 3) of one layer
+    def time_call(fn, reps=32, replays=5):   # a graph of `reps` calls: the host's per-call cost stays out of the figure
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        sync()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn()
+        g.replay()
+        sync()
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        sync()
+        return e0.elapsed_time(e1) * 1e3 / (reps * replays)
+
+    vocab = 126464
+    vl = [torch.randn(w.n_gen, vocab, device=dev).mul_(3.0).to(torch.bfloat16) for _ in range(4)]   # 4 x 16 MB, rotated
+    tok_buf = torch.empty(w.n_gen, dtype=torch.int32, device=dev)
+    conf_buf = torch.empty(w.n_gen, dtype=torch.float32, device=dev)
+    conf_ws = torch.empty(max(fb.token_confidence_workspace(w.n_gen, vocab), 16), dtype=torch.uint8, device=dev)
+    rot = [0]
+
+    def conf_call():
+        rot[0] = (rot[0] + 1) % len(vl)
+        fb.token_confidence(vl[rot[0]], masked, tok_buf, conf_buf, conf_ws)
+    us = time_call(conf_call)
+    cb = w.n_gen * vocab * 2
+    stages["token_confidence"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": cb, "alg_flops": 0,
+                                  "GBps": round(cb / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(cb / us * 1e-3 / HBM_PEAK_GBS, 4),
+                                  "shape": f"{w.n_gen} x {vocab} bf16 logits"}
+    q0, k0, v0 = st0.layers[0]
+    k_new = torch.randn(H, st0.max_active, d, device=dev).to(torch.bfloat16)
+    v_new = torch.randn(H, st0.max_active, d, device=dev).to(torch.bfloat16)
+    k_cache, v_cache = k0.clone(), v0.clone()
+    s_cache = fb.make_shape(q0, k_cache, v_cache, M, w.block)
+    us = time_call(lambda: fb.cache_update(k_cache, v_cache, s_cache, k_new, v_new, st0.active_idx, st0.counts, M))
+    ub = 2 * 2 * n_q * H * d * 2
+    stages["cache_update"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": ub, "alg_flops": 0,
+                              "GBps": round(ub / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(ub / us * 1e-3 / HBM_PEAK_GBS, 4)}
+    del vl, k_cache, v_cache
+
     # the stage that takes the largest share of the timed step
     # (the step calls focus_sparse_layer; its parts are also timed through the separate entry points, which run the same kernels)
     in_step = ("select", "find_sinks", "block_partials", "sparse_attn")

@@ -189,6 +189,37 @@ int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* c
                       const void* K, const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse,
                       float* col_mass, int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Predicted token and confidence of every position of the generation block (Sec. 3, Eq. 2): the input of Eq. 4.
+ *   logits  [dev] bf16 [n_rows, vocab], row i at logits + i * row_stride (elements; a multiple of 8, rows 16-byte
+ *           aligned); entries finite or -inf, no NaN
+ *   masked  [dev] uint8[n_rows] or NULL (= all): rows with masked[i] == 0 get tokens[i] = -1, conf[i] = 0
+ *   tokens  [dev] int32[n_rows] out: argmax over the vocabulary, the lower id on a tie
+ *   conf    [dev] fp32[n_rows] out: softmax probability of that token, 1 / sum_v exp(logit_v - max) in fp32
+ *   workspace  [dev] focus_token_confidence_workspace(n_rows, vocab) bytes, 16-byte aligned (long rows are cut into
+ *           several workgroups whose partial results meet there)
+ * conf can be handed to focus_select_queries as it is.  1 <= n_rows <= 65535.
+ */
+int focus_token_confidence(const void* logits, int64_t row_stride, const uint8_t* masked, int32_t n_rows,
+                           int32_t vocab, int32_t* tokens, float* conf, void* workspace, size_t ws_bytes,
+                           void* stream);
+/* Bytes of workspace focus_token_confidence needs; 0 on invalid arguments.  [host] only. */
+size_t focus_token_confidence_workspace(int32_t n_rows, int32_t vocab);
+
+/*
+ * Approximate KV cache update (Sec. 3, Eq. 3; Alg. 1 "Update KV Cache for indices in I_active"): the cache rows of
+ * the refreshed positions take the newly computed states, every other row is left as it is.
+ *   K_cache, V_cache [dev] bf16 [H, M+N, d], strides k_/v_stride_* of `shape`, updated in place
+ *   K_new, V_new     [dev] bf16 [H, max_active, d] with strides new_stride_h / new_stride_n (elements, multiples of 8):
+ *                    slot a holds the new state of position active_idx[a]
+ *   active_idx, counts, max_active   as in focus_sparse_attn (counts[1] valid entries; NULL = all)
+ *   row_base         cache row of position 0 of the generation block (M when the block starts the response)
+ * Entries < 0 or mapping outside [0, M+N) are skipped.  Repeated entries: the last writer is unspecified.
+ */
+int focus_cache_update(void* K_cache, void* V_cache, const focus_shape* shape, const void* K_new, const void* V_new,
+                       int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
+                       int32_t max_active, int32_t row_base, void* stream);
+
 /* Bytes of workspace `fn` needs for this shape; 0 on invalid arguments.  [host] only. */
 size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep,
                              int32_t n_sink);

@@ -20,6 +20,7 @@ FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER 
 
 EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
            "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer",
+           "focus_token_confidence", "focus_token_confidence_workspace", "focus_cache_update",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
 
@@ -57,11 +58,15 @@ def lib() -> C.CDLL:
         L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
         L.focus_probe_layer.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, p, p, sz, p]
+        L.focus_token_confidence.argtypes = [p, C.c_int64, p, i32, i32, p, p, p, sz, p]
+        L.focus_token_confidence_workspace.argtypes = [i32, i32]
+        L.focus_token_confidence_workspace.restype = sz
+        L.focus_cache_update.argtypes = [p, p, sp, p, p, C.c_int64, C.c_int64, p, p, i32, i32, p]
         L.focus_block_partials.argtypes = [p, p, p, i32, p, p, sp, p, p]
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
                      "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
-                     "focus_probe_layer"):
+                     "focus_probe_layer", "focus_token_confidence", "focus_cache_update"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
         L.focus_workspace_bytes.restype = sz
@@ -194,6 +199,31 @@ def probe_layer(q, active_idx, counts, k, v, shape: Shape, n_sink: int, out, lse
                                    C.byref(shape), n_sink, _ptr(out), _ptr(lse), _ptr(col_mass), _ptr(sink_idx),
                                    _ptr(workspace),
                                    0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def token_confidence_workspace(n_rows: int, vocab: int) -> int:
+    return int(lib().focus_token_confidence_workspace(n_rows, vocab))
+
+
+def token_confidence(logits, masked, tokens, conf, workspace) -> None:
+    """logits bf16 [n_rows, vocab] (row stride a multiple of 8); workspace of token_confidence_workspace() bytes."""
+    _need(logits, torch.bfloat16, "logits")
+    _need(conf, torch.float32, "conf")
+    if logits.stride(1) != 1:
+        raise ValueError("logits: innermost stride must be 1")
+    _check(lib().focus_token_confidence(_ptr(logits), logits.stride(0), _ptr(masked), logits.shape[0], logits.shape[1],
+                                        _ptr(tokens), _ptr(conf), _ptr(workspace),
+                                        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def cache_update(k_cache, v_cache, shape: Shape, k_new, v_new, active_idx, counts, row_base: int) -> None:
+    """k_cache, v_cache bf16 [H, M+N, d] (strides from `shape`), k_new, v_new bf16 [H, max_active, d]."""
+    for t, name in ((k_cache, "K_cache"), (v_cache, "V_cache"), (k_new, "K_new"), (v_new, "V_new")):
+        _need(t, torch.bfloat16, name)
+    if k_new.stride() != v_new.stride() or k_new.stride(2) != 1:
+        raise ValueError("K_new and V_new must share their strides, innermost 1")
+    _check(lib().focus_cache_update(_ptr(k_cache), _ptr(v_cache), C.byref(shape), _ptr(k_new), _ptr(v_new), k_new.stride(0),
+                                    k_new.stride(1), _ptr(active_idx), _ptr(counts), active_idx.numel(), row_base, _stream()))
 
 
 def sparse_layer(q, focus_idx, active_idx, counts, k, v, kbar, shape: Shape, n_keep: int, sink_idx, n_sink: int, scores,

@@ -365,6 +365,43 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   return FOCUS_OK;
 }
 
+size_t focus_token_confidence_workspace(int32_t n_rows, int32_t vocab) {
+  if (n_rows < 1 || n_rows > 65535 || vocab < 1) return 0;
+  return std::max<size_t>(token_confidence_workspace(n_rows, vocab), 16);
+}
+
+int focus_token_confidence(const void* logits, int64_t row_stride, const uint8_t* masked, int32_t n_rows, int32_t vocab,
+                           int32_t* tokens, float* conf, void* workspace, size_t ws_bytes, void* stream) {
+  if (!logits || !tokens || !conf) return fail(FOCUS_EINVAL, "focus_token_confidence: NULL pointer");
+  if (n_rows < 1 || n_rows > 65535) return fail(FOCUS_EINVAL, "focus_token_confidence: n_rows=%d not in [1, 65535]", n_rows);
+  if (vocab < 1) return fail(FOCUS_EINVAL, "focus_token_confidence: vocab=%d", vocab);
+  if (row_stride < vocab || (row_stride & 7) || !aligned16(logits))
+    return fail(FOCUS_EINVAL, "focus_token_confidence: rows must be 16-byte aligned (row_stride a multiple of 8, >= vocab)");
+  const size_t need = token_confidence_workspace(n_rows, vocab);
+  if (need > 0 && (!workspace || ws_bytes < need || !aligned16(workspace)))
+    return fail(FOCUS_EWORKSPACE, "focus_token_confidence: workspace needs %zu bytes, 16-byte aligned", need);
+  hipError_t e = launch_token_confidence(logits, row_stride, masked, n_rows, vocab, tokens, conf, workspace,
+                                         static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_token_confidence", e);
+  return FOCUS_OK;
+}
+
+int focus_cache_update(void* K_cache, void* V_cache, const focus_shape* shape, const void* K_new, const void* V_new,
+                       int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
+                       int32_t max_active, int32_t row_base, void* stream) {
+  if (int rc = check_shape(shape, false, true, true, false)) return rc;
+  if (!K_cache || !V_cache || !K_new || !V_new || !active_idx) return fail(FOCUS_EINVAL, "focus_cache_update: NULL pointer");
+  if (max_active < 1 || max_active > 65535) return fail(FOCUS_EINVAL, "focus_cache_update: max_active=%d not in [1, 65535]", max_active);
+  if (new_stride_n < shape->head_dim || (new_stride_n & 7) || new_stride_h < 0 || (new_stride_h & 7))
+    return fail(FOCUS_EINVAL, "focus_cache_update: strides of the new states invalid or not multiples of 8");
+  if (!aligned16(K_cache) || !aligned16(V_cache) || !aligned16(K_new) || !aligned16(V_new))
+    return fail(FOCUS_EINVAL, "focus_cache_update: pointers must be 16-byte aligned");
+  hipError_t e = launch_cache_update(K_cache, V_cache, *shape, K_new, V_new, new_stride_h, new_stride_n, active_idx, counts,
+                                     max_active, row_base, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_cache_update", e);
+  return FOCUS_OK;
+}
+
 int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active, const void* K,
                       const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse, float* col_mass,
                       int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream) {

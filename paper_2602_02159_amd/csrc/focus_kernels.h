@@ -59,6 +59,16 @@ hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* l
 hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st);
 
+// Eq. 2: tokens[i] = argmax over the vocabulary of row i of the bf16 logits, conf[i] = its softmax probability
+// (workspace of token_confidence_workspace() bytes: per-split states when a row is cut into several workgroups)
+size_t token_confidence_workspace(int n_rows, int vocab);
+hipError_t launch_token_confidence(const void* logits, int64_t row_stride, const uint8_t* masked, int n_rows, int vocab,
+                                   int32_t* tokens, float* conf, void* workspace, hipStream_t st);
+// Eq. 3: scatter the new K/V states of the active positions into the cache (strides of the cache from the shape)
+hipError_t launch_cache_update(void* K_cache, void* V_cache, const focus_shape& s, const void* K_new, const void* V_new,
+                               int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
+                               int max_active, int row_base, hipStream_t st);
+
 // ---- MFMA kernels (focus_mfma.hip)
 // mode 0: logits [H, L, q_pad] + part_ml out; mode 1: part_ml out only; mode 2: lse2 in, colpart [q_groups * H, L] out
 hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,

@@ -524,4 +524,181 @@ hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, 
   return hipGetLastError();
 }
 
+// =====================================================================================================
+// Around the step (Sec. 3): confidence from the vocabulary logits (Eq. 2) and the approximate KV cache (Eq. 3).
+// =====================================================================================================
+// Running state of one softmax row: maximum m, lowest index of the maximum, and s = sum exp(x - m).
+struct ConfState {
+  float m;
+  int idx;
+  float s;
+};
+// merge in the order (value descending, index ascending); s is rescaled to the larger maximum
+__device__ __forceinline__ ConfState conf_merge(const ConfState& a, const ConfState& b) {
+  ConfState r;
+  const bool a_first = a.m > b.m || (a.m == b.m && a.idx < b.idx);
+  r.m = a_first ? a.m : b.m;
+  r.idx = a_first ? a.idx : b.idx;
+  const float sa = a.s > 0.f ? a.s * __expf(a.m - r.m) : 0.f;  // s == 0 marks "nothing seen": its m is -inf
+  const float sb = b.s > 0.f ? b.s * __expf(b.m - r.m) : 0.f;
+  r.s = sa + sb;
+  return r;
+}
+
+// x_hat = argmax_v logit_v (ties to the lower id), c = 1 / sum_v exp(logit_v - max).  Workgroup (row, split) walks one
+// contiguous slice of the row once: eight bf16 per 16-byte non-temporal load; per vector the running maximum is raised
+// once and the eight exponentials are added.  Threads, then wavefronts, merge their states in a fixed order.  With
+// one split the workgroup writes the result; otherwise its state goes to part[row, split] and token_confidence_merge
+// finishes the row (splits in index order).
+__global__ __launch_bounds__(256) void token_confidence_kernel(const uint16_t* __restrict__ logits, int64_t row_stride,
+                                                               const uint8_t* __restrict__ masked, int vocab, int n_split,
+                                                               ConfState* __restrict__ part, int32_t* __restrict__ tokens,
+                                                               float* __restrict__ conf) {
+  __shared__ ConfState wave_state[4];
+  const int row = blockIdx.x, split = blockIdx.y, tid = threadIdx.x, nt = blockDim.x;
+  ConfState st;
+  st.m = -INFINITY;
+  st.idx = 0x7fffffff;
+  st.s = 0.f;
+  const bool skip = masked != nullptr && masked[row] == 0;  // uniform over the workgroup
+  if (!skip) {
+    const uint16_t* x = logits + (int64_t)row * row_stride;
+    const int n_vec = vocab >> 3;
+    const int per = (n_vec + n_split - 1) / n_split;
+    const int v_begin = split * per, v_end = min(v_begin + per, n_vec);
+    for (int v0 = v_begin + tid; v0 < v_end; v0 += nt * 2) {  // two vectors in flight
+      const int v1 = v0 + nt;
+      const uint4 a = load_stream16(x + (int64_t)v0 * 8);
+      const uint4 b = v1 < v_end ? load_stream16(x + (int64_t)v1 * 8) : make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
+      const uint4 vv[2] = {a, b};
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const uint32_t w[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+        float e[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          e[2 * i] = bf16_lo(w[i]);
+          e[2 * i + 1] = bf16_hi(w[i]);
+        }
+        float vm = e[0];
+        int vi = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) {
+          if (e[i] > vm) {  // strict: the lowest position of the vector's maximum
+            vm = e[i];
+            vi = i;
+          }
+        }
+        if (vm > st.m) {  // vectors arrive in ascending index order, so a strict test keeps the lowest index
+          st.s = st.s > 0.f ? st.s * __expf(st.m - vm) : 0.f;
+          st.m = vm;
+          st.idx = (u == 0 ? v0 : v1) * 8 + vi;
+        }
+        if (st.m > -INFINITY) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) st.s += __expf(e[i] - st.m);
+        }
+      }
+    }
+    if (split == n_split - 1) {  // ragged tail of the row, one element per thread
+      for (int j = (n_vec << 3) + tid; j < vocab; j += nt) {
+        const float e = bf16_lo((uint32_t)x[j]);
+        if (e > st.m) {
+          st.s = st.s > 0.f ? st.s * __expf(st.m - e) : 0.f;
+          st.m = e;
+          st.idx = j;
+        }
+        if (st.m > -INFINITY) st.s += __expf(e - st.m);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {  // butterfly: every lane ends with the wavefront's state
+    ConfState other;
+    other.m = __shfl_xor(st.m, o, kWave);
+    other.idx = __shfl_xor(st.idx, o, kWave);
+    other.s = __shfl_xor(st.s, o, kWave);
+    st = conf_merge(st, other);
+  }
+  if ((tid & 63) == 0) wave_state[tid >> 6] = st;
+  __syncthreads();
+  if (tid == 0) {
+    ConfState r = wave_state[0];
+    for (int w = 1; w < (nt >> 6); ++w) r = conf_merge(r, wave_state[w]);
+    if (n_split == 1) {
+      tokens[row] = r.s > 0.f ? r.idx : -1;
+      conf[row] = r.s > 0.f ? 1.f / r.s : 0.f;
+    } else {
+      part[(int64_t)row * n_split + split] = r;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void token_confidence_merge(const ConfState* __restrict__ part, int n_rows, int n_split,
+                                                              int32_t* __restrict__ tokens, float* __restrict__ conf) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= n_rows) return;
+  ConfState r = part[(int64_t)row * n_split];
+  for (int s = 1; s < n_split; ++s) r = conf_merge(r, part[(int64_t)row * n_split + s]);
+  tokens[row] = r.s > 0.f ? r.idx : -1;
+  conf[row] = r.s > 0.f ? 1.f / r.s : 0.f;
+}
+
+// splits per row: enough workgroups to fill the chip, at least 64 vectors each
+int token_confidence_splits(int n_rows, int vocab) {
+  const int by_rows = ceil_div(1024, n_rows);
+  const int by_work = std::max(1, (vocab >> 3) / 512);
+  return std::max(1, std::min(std::min(by_rows, by_work), 32));
+}
+size_t token_confidence_workspace(int n_rows, int vocab) {
+  const int n_split = token_confidence_splits(n_rows, vocab);
+  return n_split > 1 ? (size_t)n_rows * n_split * sizeof(ConfState) : 0;
+}
+
+hipError_t launch_token_confidence(const void* logits, int64_t row_stride, const uint8_t* masked, int n_rows, int vocab,
+                                   int32_t* tokens, float* conf, void* workspace, hipStream_t st) {
+  const int n_split = token_confidence_splits(n_rows, vocab);
+  ConfState* part = static_cast<ConfState*>(workspace);
+  hipLaunchKernelGGL(token_confidence_kernel, dim3(n_rows, n_split), dim3(256), 0, st, static_cast<const uint16_t*>(logits),
+                     row_stride, masked, vocab, n_split, part, tokens, conf);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_split == 1) return e;
+  hipLaunchKernelGGL(token_confidence_merge, dim3(ceil_div(n_rows, 256)), dim3(256), 0, st, part, n_rows, n_split, tokens, conf);
+  return hipGetLastError();
+}
+
+// Eq. 3: cache rows row_base + active_idx[a] of K and V take the new states K_new[:, a], V_new[:, a].  One workgroup
+// per (active slot, head); a thread moves one 16-byte chunk of the K or of the V row.  Entries outside the active
+// count, negative, or mapping outside [0, n_rows) are skipped.
+__global__ __launch_bounds__(64) void cache_update_kernel(uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, int64_t ksh,
+                                                          int64_t ksn, int64_t vsh, int64_t vsn,
+                                                          const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
+                                                          int64_t nsh, int64_t nsn, const int32_t* __restrict__ active_idx,
+                                                          const int32_t* __restrict__ counts, int max_active, int row_base,
+                                                          int n_rows, int chunks) {
+  const int a = blockIdx.x, h = blockIdx.y;
+  const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
+  if (a >= n_act) return;
+  const int i = active_idx[a];
+  const int64_t row = (int64_t)row_base + i;
+  if (i < 0 || row < 0 || row >= n_rows) return;
+  for (int t = threadIdx.x; t < 2 * chunks; t += blockDim.x) {
+    const bool is_v = t >= chunks;
+    const int c = is_v ? t - chunks : t;
+    const uint16_t* src = (is_v ? Vn : Kn) + (int64_t)h * nsh + (int64_t)a * nsn + c * 8;
+    uint16_t* dst = is_v ? Vc + (int64_t)h * vsh + row * vsn + c * 8 : Kc + (int64_t)h * ksh + row * ksn + c * 8;
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  }
+}
+
+hipError_t launch_cache_update(void* K_cache, void* V_cache, const focus_shape& s, const void* K_new, const void* V_new,
+                               int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
+                               int max_active, int row_base, hipStream_t st) {
+  hipLaunchKernelGGL(cache_update_kernel, dim3(max_active, s.n_heads), dim3(64), 0, st, static_cast<uint16_t*>(K_cache),
+                     static_cast<uint16_t*>(V_cache), s.k_stride_h, s.k_stride_n, s.v_stride_h, s.v_stride_n,
+                     static_cast<const uint16_t*>(K_new), static_cast<const uint16_t*>(V_new), new_stride_h, new_stride_n,
+                     active_idx, counts, max_active, row_base, s.n_ctx + s.n_resp, s.head_dim / 8);
+  return hipGetLastError();
+}
+
 }  // namespace focus

@@ -451,3 +451,67 @@ def test_stack_reuses_probe_layer_sinks(G):
         assert torch.equal(sinks, frozen)                              # reused unchanged
         assert kept.cpu().tolist() == step["layers"][l]["blocks"].tolist()
         G.assert_attention_close(out, step["layers"][l]["out"])
+
+
+# ------------------------------------------------------------------------------------------------ around the step
+@pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
+def test_token_confidence(G, n_rows, vocab, pad):
+    """Eq. 2 on bf16 logits: the arg max is exact (bf16 rows hold many exactly equal maxima: the lower id wins), the
+    confidence agrees with the float64 oracle to fp32 summation accuracy."""
+    stride = -(-(vocab + pad) // 8) * 8
+    g = torch.Generator().manual_seed(90 + vocab)
+    buf = (torch.randn(n_rows, stride, generator=g) * 3.0).to(torch.bfloat16)
+    buf[0, : vocab // 2] = buf[0, : vocab // 2].clamp(max=2.0)             # a plateau: thousands of tokens share the maximum
+    if n_rows > 2:
+        buf[2, ::3] = float("-inf")                                         # excluded tokens
+    logits = buf.to(G.DEV)[:, :vocab]
+    masked = (torch.arange(n_rows) % 4 != 1).to(torch.uint8)
+    for m in (None, masked):
+        tok = G.i32(None, n_rows)
+        conf = torch.full((n_rows,), float("nan"), dtype=torch.float32, device=G.DEV)
+        w = G.ws(fb.token_confidence_workspace(n_rows, vocab))
+        w.fill_(0xEE)
+        fb.token_confidence(logits, None if m is None else m.to(G.DEV), tok, conf, w)
+        torch.cuda.synchronize()
+        ref_tok, ref_conf = fo.token_confidence(G.to_np(logits), None if m is None else m.numpy())
+        assert tok.cpu().tolist() == ref_tok.tolist()
+        assert np.allclose(conf.cpu().numpy(), ref_conf, rtol=2e-5, atol=0)
+    # the result is the input of Eq. 4 as it stands
+    focus, _, _ = G.gpu_select(conf.cpu().numpy(), masked.numpy(), min(2, n_rows), 0, 0, n_rows)
+    assert focus.cpu().tolist()[: len(fo.select_focus(ref_conf, masked.numpy(), min(2, n_rows)))] == \
+        fo.select_focus(ref_conf.astype(np.float32), masked.numpy(), min(2, n_rows)).tolist()
+
+
+def test_token_confidence_uniform_row(G):
+    logits = torch.zeros(2, 4096, dtype=torch.bfloat16, device=G.DEV)
+    tok, conf = G.i32(None, 2), torch.zeros(2, dtype=torch.float32, device=G.DEV)
+    fb.token_confidence(logits, None, tok, conf, G.ws(fb.token_confidence_workspace(2, 4096)))
+    torch.cuda.synchronize()
+    assert tok.cpu().tolist() == [0, 0] and np.allclose(conf.cpu().numpy(), 1.0 / 4096, rtol=1e-6)
+
+
+@pytest.mark.parametrize("H,M,N,d,cap,n_act,base", [(4, 100, 32, 64, 8, 5, 100), (32, 2048, 64, 128, 36, 28, 2048 + 16), (2, 64, 16, 128, 16, 16, 64)])
+def test_cache_update(G, H, M, N, d, cap, n_act, base):
+    """Eq. 3: exactly the rows of the refreshed positions change, bit for bit; strided cache layout, spare slots,
+    negative and out-of-range entries are skipped."""
+    rng = np.random.default_rng(H + M)
+    L = M + N
+    kc = _rand_bf16(95, L, H, d).to(G.DEV).permute(1, 0, 2)                  # cache stored [L, H, d]
+    vc = _rand_bf16(96, H, L, d).to(G.DEV)
+    kn, vn = _rand_bf16(97, H, cap, d).to(G.DEV), _rand_bf16(98, H, cap, d).to(G.DEV)
+    span = L - base
+    act = np.sort(rng.choice(span, min(n_act, span), replace=False)).tolist()
+    lst = act + [-1] * (cap - len(act))
+    if len(act) < cap:
+        lst[len(act)] = 3                                                    # a stale entry past the count must be ignored
+    k_before, v_before = kc.clone(), vc.clone()
+    s = fb.make_shape(kn, kc, vc, M, 64)
+    fb.cache_update(kc, vc, s, kn, vn, G.i32(lst), G.i32([0, len(act)]), base)
+    torch.cuda.synchronize()
+    K_ref, V_ref = fo.cache_update(G.to_np(k_before), G.to_np(v_before), G.to_np(kn), G.to_np(vn), act, base)
+    assert np.array_equal(G.to_np(kc), K_ref) and np.array_equal(G.to_np(vc), V_ref)
+    # entries that map outside the cache or are negative: nothing happens
+    k2, v2 = kc.clone(), vc.clone()
+    fb.cache_update(kc, vc, s, kn, vn, G.i32([-5, span, span + 7] + [-1] * (cap - 3)), None, base)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, k2) and torch.equal(vc, v2)

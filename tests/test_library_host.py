@@ -88,6 +88,15 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 17, fake, fake, None) == fb.FOCUS_EINVAL
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, None, fake, None) == fb.FOCUS_EINVAL
     assert L.focus_top_blocks(fake, 4, None, 8, 16, 4, fake, None, None) == fb.FOCUS_EINVAL
+    # confidence: NULL output, misaligned rows, bad stride; cache update: NULL pointer, bad stride of the new states
+    assert L.focus_token_confidence(fake, 1000, None, 4, 1000, None, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_token_confidence(fake, 1001, None, 4, 1000, fake, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_token_confidence(fake, 992, None, 4, 1000, fake, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_token_confidence(fake, 1000, None, 0, 1000, fake, fake, fake, big, None) == fb.FOCUS_EINVAL
+    assert L.focus_token_confidence(fake, 131072, None, 64, 131072, fake, fake, None, 0, None) == fb.FOCUS_EWORKSPACE
+    assert fb.token_confidence_workspace(64, 131072) >= 64 * 16 * 12 and fb.token_confidence_workspace(0, 10) == 0
+    assert L.focus_cache_update(fake, None, sp, fake, fake, 512, 64, fake, None, 8, 1024, None) == fb.FOCUS_EINVAL
+    assert L.focus_cache_update(fake, fake, sp, fake, fake, 512, 60, fake, None, 8, 1024, None) == fb.FOCUS_EINVAL
     # probe layer: NULL V, n_sink out of range, workspace too small
     assert L.focus_probe_layer(fake, fake, None, 8, fake, None, sp, 2, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_probe_layer(fake, fake, None, 8, fake, fake, sp, 5000, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
