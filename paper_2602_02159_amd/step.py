@@ -20,11 +20,15 @@ class FocusStep:
 
     Layers are (q, k, v) bf16 CUDA tensors in [H, rows, d] layout: q [H, n_gen, d]; k, v [H, M+N, d].
     `probe` is the (q, k) pair of the layer whose attention identifies the sinks, or its (q, k, v) triple: then the
-    stage "probe_layer" (that layer's dense attention and the sinks in one call) is available as well.
+    stage "probe_layer" (that layer's dense attention and the sinks in one call) is available as well and, with
+    `use_probe_layer`, replaces "find_sinks" in the step.
+    `logits` (bf16 [n_gen, vocab], optional): the step then starts with focus_token_confidence, whose output is the
+    confidence the query selection ranks (`conf` is overwritten).
+    `dense_tail`: the last so many layers attend to every block (the schedule that keeps the final layers dense).
     """
 
     def __init__(self, conf, masked, probe, sparse_layers, n_ctx: int, block: int, k_focus: int, window: int, n_keep: int,
-                 n_sink: int, cached_means: bool = False, dense: bool = False):
+                 n_sink: int, cached_means: bool = False, dense: bool = False, logits=None, dense_tail: int = 0):
         q0 = probe[0]
         dev = q0.device
         self.H, self.n_gen, self.d = q0.shape
@@ -37,6 +41,8 @@ class FocusStep:
         self.col_mass = torch.empty(probe[1].shape[1], dtype=torch.float32, device=dev)
         self.all_blocks = torch.arange(self.n_b, dtype=torch.int32, device=dev)
         self.conf, self.masked, self.probe, self.layers = conf, masked, probe, list(sparse_layers)
+        self.dense_tail, self.use_probe_layer = dense_tail, False
+        self.tokens = i32(self.n_gen)
         self.bufs = [{
             "kept": i32(n_keep),
             "scores": torch.empty(self.n_b, dtype=torch.float32, device=dev),
@@ -103,6 +109,13 @@ class FocusStep:
             self.calls["dense_attn"].append((L.focus_sparse_attn, (
                 p(q), p(self.active_idx), p(self.counts), self.max_active, p(k), p(v), sp, p(self.all_blocks), self.n_b,
                 None, 0, p(b["out"]), None, p(ws_dense), ws_dense.numel())))
+        self.calls["confidence"] = []
+        if logits is not None:
+            ws_conf = workspace(fb.token_confidence_workspace(logits.shape[0], logits.shape[1]))
+            self.calls["confidence"] = [(L.focus_token_confidence, (
+                p(logits), logits.stride(0), p(masked), logits.shape[0], logits.shape[1], p(self.tokens), p(conf), p(ws_conf),
+                ws_conf.numel()))]
+            self._keep.append(logits)
         self.cached_means, self.dense, self.fused = cached_means, dense, True
         self._graph = None
 
@@ -119,16 +132,20 @@ class FocusStep:
         self._issue(calls if layer is None else calls[layer:layer + 1], torch.cuda.current_stream().cuda_stream)
 
     def sequence(self):
-        """The step's calls in order: queries once, sinks once at the probe layer, then every sparse layer."""
-        seq = self.calls["select"] + self.calls["find_sinks"]
+        """The step's calls in order: [confidence,] queries once, sinks once at the probe layer, then every layer."""
+        seq = self.calls["confidence"] + self.calls["select"]
+        seq = seq + (self.calls["probe_layer"] if self.use_probe_layer and self.calls["probe_layer"] else self.calls["find_sinks"])
         if self.dense:
             return seq + self.calls["dense_attn"]
+        n = len(self.layers)
+        first_dense = n - min(self.dense_tail, n)
         if self.fused:  # one call per sparse layer: block scores and attention in three launches
-            return seq + self.calls["sparse_layer_cached" if self.cached_means else "sparse_layer"]
+            per_layer = self.calls["sparse_layer_cached" if self.cached_means else "sparse_layer"]
+            return seq + per_layer[:first_dense] + self.calls["dense_attn"][first_dense:]
         scores = self.calls["block_scores_cached" if self.cached_means else "block_scores"]
-        for i in range(len(self.layers)):
+        for i in range(first_dense):
             seq = seq + [scores[i], self.calls["sparse_attn"][i]]
-        return seq
+        return seq + self.calls["dense_attn"][first_dense:]
 
     def run(self):
         """Enqueue one whole step (eagerly, or by replaying the captured graph)."""

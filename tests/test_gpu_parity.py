@@ -453,6 +453,62 @@ def test_stack_reuses_probe_layer_sinks(G):
         G.assert_attention_close(out, step["layers"][l]["out"])
 
 
+def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
+    """The whole step as the driver sequences it and a HIP graph replays it: confidence from logits, query selection,
+    the probe layer's dense attention with the sinks as a by-product, sparse layers, and a dense last layer."""
+    from paper_2602_02159_amd.step import FocusStep
+    w = fi.strong_sinks(fi.TINY).with_(n_layers=5, probe_layer=1, first_sparse_layer=2, window=2)
+    tensors = {l: tuple(t.to(G.DEV) for t in fi.layer_qkv(w, l)) for l in range(w.n_layers)}
+    vocab = 5003
+    g = torch.Generator().manual_seed(123)
+    logits = (torch.randn(w.n_gen, vocab + 5, generator=g) * 2.5).to(torch.bfloat16).to(G.DEV)[:, :vocab]
+    masked = (torch.arange(w.n_gen) % 5 != 0).to(torch.uint8)
+    conf = torch.zeros(w.n_gen, dtype=torch.float32, device=G.DEV)
+    st = FocusStep(conf, masked.to(G.DEV), tensors[w.probe_layer], [tensors[l] for l in (2, 3, 4)], w.n_ctx, w.block,
+                   w.k_focus, w.window, w.n_keep, w.n_sink, logits=logits, dense_tail=1)
+    st.use_probe_layer = True
+    # oracle
+    tok_ref, conf_ref = fo.token_confidence(G.to_np(logits), masked.numpy())
+    focus_ref = fo.select_focus(conf_ref.astype(np.float32), masked.numpy(), w.k_focus)
+    active_ref = fo.expand_window(focus_ref, w.window, 0, w.n_gen)
+    np_l = {l: tuple(G.to_np(t) for t in tensors[l]) for l in tensors}
+    Qp, Kp, Vp = np_l[w.probe_layer]
+    sinks_ref = fo.select_sinks(fo.sink_scores(Qp, active_ref, Kp), w.n_ctx, w.n_sink)
+    probe_ref, _ = fo.sparse_attention(Qp, active_ref, Kp, Vp, np.arange(w.n_ctx), w.n_ctx)
+    lay_ref = [fo.focus_layer(*np_l[l], focus_ref, active_ref, sinks_ref, w.n_ctx, w.block, w.n_keep) for l in (2, 3)]
+    dense_ref, _ = fo.sparse_attention(*np_l[4][:1], active_ref, *np_l[4][1:], np.arange(w.n_ctx), w.n_ctx)
+
+    def check():
+        n_a = len(active_ref)
+        assert st.tokens.cpu().tolist() == tok_ref.tolist()
+        assert np.allclose(st.conf.cpu().numpy(), conf_ref, rtol=2e-5)
+        assert st.counts.cpu().tolist() == [len(focus_ref), n_a]
+        assert st.focus_idx.cpu().tolist()[:len(focus_ref)] == focus_ref.tolist()
+        assert st.active_idx.cpu().tolist()[:n_a] == active_ref.tolist()
+        assert st.sink_idx.cpu().tolist() == sinks_ref.tolist() == list(w.sink_positions)
+        G.assert_attention_close(st.probe_out[:, :n_a], probe_ref)
+        for i in range(2):
+            assert st.bufs[i]["kept"].cpu().tolist() == lay_ref[i]["blocks"].tolist()
+            G.assert_attention_close(st.bufs[i]["out"][:, :n_a], lay_ref[i]["out"])
+        G.assert_attention_close(st.bufs[2]["out"][:, :n_a], dense_ref)
+
+    st.run()
+    torch.cuda.synchronize()
+    check()
+    eager = [b["out"].clone() for b in st.bufs]
+    st.capture()
+    for _ in range(3):                                   # replays, with the buffers wiped in between
+        for b in st.bufs:
+            b["out"].zero_()
+        st.conf.zero_()
+        st.sink_idx.fill_(-3)
+        torch.cuda.synchronize()
+        st.run()
+        torch.cuda.synchronize()
+        check()
+        assert all(torch.equal(a, b["out"]) for a, b in zip(eager, st.bufs))
+
+
 # ------------------------------------------------------------------------------------------------ around the step
 @pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
 def test_token_confidence(G, n_rows, vocab, pad):
