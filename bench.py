@@ -144,6 +144,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=4)
+    ap.add_argument("--full-refresh", action="store_true",
+                    help="also time one layer of a block-entry refresh: dense attention of all M+N positions (the MFMA-bound case)")
     ap.add_argument("--mode", default="bench", choices=["bench", "pmc"],
                     help="pmc: run a 1 GiB copy (calibration) and a few launches of every stage, nothing else; meant to be "
                          "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
@@ -380,6 +382,30 @@ def main() -> int:
     stages["cache_update"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": ub, "alg_flops": 0,
                               "GBps": round(ub / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(ub / us * 1e-3 / HBM_PEAK_GBS, 4)}
     del vl, k_cache, v_cache
+    if args.full_refresh:
+        # block entry (Alg. 1): every position is active and attends to every key; 4 L^2 d H flops against the bf16 MFMA peak
+        q_all = torch.randn(H, L, d, device=dev).to(torch.bfloat16)
+        out_all = torch.empty(H, L, d, dtype=torch.bfloat16, device=dev)
+        act_all = torch.arange(L, dtype=torch.int32, device=dev)
+        blocks_all = torch.arange(n_b, dtype=torch.int32, device=dev)
+        s_all = fb.make_shape(q_all, k0, v0, M, w.block, out_all)
+        ws_all = torch.empty(max(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s_all, L, n_b, 0), 256), dtype=torch.uint8, device=dev)
+        call = lambda: fb.sparse_attn(q_all, act_all, None, k0, v0, s_all, blocks_all, n_b, None, 0, out_all, None, ws_all)
+        call()
+        sync()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            call()
+        e1.record()
+        sync()
+        us = e0.elapsed_time(e1) * 1e3 / 3
+        fl = 4 * L * L * d * H
+        stages["full_refresh_layer"] = {"us_per_launch": round(us, 1), "launches_per_step": 0, "alg_bytes": int(2 * 2 * L * H * d * 2),
+                                        "alg_flops": int(fl), "GBps": round(2 * 2 * L * H * d * 2 / us * 1e-3, 1),
+                                        "TFLOPps": round(fl / us * 1e-6, 1), "mfma_frac": round(fl / us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                        "bound": "mfma"}
+        del q_all, out_all, ws_all
 
     # the stage that takes the largest share of the timed step
     # (the step calls focus_sparse_layer; its parts are also timed through the separate entry points, which run the same kernels)

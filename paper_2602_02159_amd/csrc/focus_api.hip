@@ -153,6 +153,11 @@ struct AttnWs {
 static AttnWs ws_attn(const focus_shape& s, const SplitPlan& p) {
   AttnWs w;
   w.part_o = 0;
+  if (p.n_split <= 1) {  // a single key split writes the output itself: no partial results
+    w.part_ml = 0;
+    w.total = 256;
+    return w;
+  }
   size_t off = align_up((size_t)s.n_heads * p.q_pad * p.n_split * s.head_dim * sizeof(float));
   w.part_ml = off;
   off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
