@@ -13,6 +13,10 @@
  *     focus_sparse_attn      per sparse layer                   -> Attn
  *     focus_sparse_layer     = focus_block_scores + focus_sparse_attn of one layer, fused into fewer launches
  *     focus_probe_layer      = dense attention of the probe layer + focus_find_sinks, sharing the QK^T work
+ *     focus_block_partials / focus_top_blocks   the two halves of focus_block_scores (head-sharded callers)
+ * and, around the step (Sec. 3):
+ *     focus_token_confidence vocabulary logits -> predicted tokens, confidences (Eq. 2): the input of the selection
+ *     focus_cache_update     new K/V states of the active positions -> KV cache (Eq. 3)
  *
  * Conventions shared by every entry point
  *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
