@@ -410,6 +410,7 @@ struct AttnArgs {
   int32_t* kept_out;      // [n_keep]
   int n_focus_max;
   // dense (probe) layer only
+  int groups_first;   // grid x = query group, z = key split (see the kernel)
   int dense_rows;     // > 0: attend to all of the first dense_rows = M + N key rows, block and sink lists unused
   float* logits_out;  // [H, L, 16] scaled base-2 logits of the (at most 16) active queries, or null
   float* lse2_out;    // [H, q_pad] base-2 log-sum-exp per row (+inf for an empty row), or null
@@ -522,7 +523,10 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x, h = blockIdx.y, qg = blockIdx.z;
+  // Grid: (key split, head, query group) — or, with several query groups, (query group, head, key split): the
+  // workgroups that run side by side then belong to one head and walk the same K/V rows at about the same time, so
+  // that each XCD's L2 serves a row to all of them after fetching it once.
+  const int split = p.groups_first ? blockIdx.z : blockIdx.x, h = blockIdx.y, qg = p.groups_first ? blockIdx.x : blockIdx.z;
   const int qt = wave % QT, kg = wave / QT;
   const int q0 = (qg * QT + qt) * kQTile;  // first position in the active list of this wavefront's query tile
   FOCUS_STAMP(0);
@@ -568,7 +572,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   int sinks_ascending = -1;
   {
     const int first_sink_sub = p.n_keep * p.sub_per_block + (p.N + kSubTile - 1) / kSubTile;
-    const int my_end = min((int)(blockIdx.x + 1) * p.per_split, p.n_sub);
+    const int my_end = min((split + 1) * p.per_split, p.n_sub);
     if (p.dense_rows == 0 && p.n_sink > 0 && my_end > first_sink_sub) {  // uniform over the workgroup
       const bool bitmap = p.n_keep > 0 && p.n_b <= kBitmapBlocks;
       const int words = bitmap ? (p.n_b + 31) >> 5 : 0;
@@ -853,7 +857,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
 
 template <int D, int QT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
-  dim3 grid(p.n_split, a.H, p.q_groups);
+  const dim3 grid = a.groups_first ? dim3(p.q_groups, a.H, p.n_split) : dim3(p.n_split, a.H, p.q_groups);
   const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) have their own pipelining
   const dim3 block(QT == 4 ? 512 : 256);
   if (a.logits_out != nullptr) {  // dense probe layer with the logits spilled; QT == 1 by construction
@@ -883,6 +887,7 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
                               float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st,
                               const DenseProbe* probe) {
   AttnArgs a;
+  a.groups_first = (p.q_groups > 1 && p.n_split <= 65535) ? 1 : 0;
   a.dense_rows = probe ? s.n_ctx + s.n_resp : 0;
   a.logits_out = probe ? probe->logits_out : nullptr;
   a.lse2_out = probe ? probe->lse2_out : nullptr;
