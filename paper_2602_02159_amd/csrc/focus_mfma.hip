@@ -1,17 +1,19 @@
 // The two MFMA kernels of the step, both built on v_mfma_f32_16x16x32_bf16 (64-lane wavefronts):
 //
 //   sparse_attn_kernel  Eq. 8 + Eq. 9: gathers the kept blocks, the sinks and the response rows of K / V and
-//                       runs a split-KV online-softmax attention of the active queries over them.
-//   qk_logits_kernel    first half of Eq. 6: scaled logits of the active queries against every key of the
-//                       probe layer, plus per-split row maxima / sums for the softmax normaliser.
+//                       runs a split-KV online-softmax attention of the active queries over them.  The same kernel
+//                       with every row kept is the dense layer (probe layer, comparison, block-entry refresh).
+//   qk_logits_kernel    Eq. 6: scaled logits of the active queries against every key of the probe layer with the
+//                       per-split row maxima / sums of the softmax normaliser, or — second pass, for more than 16
+//                       queries — the probabilities summed over the queries.
 //
-// Work decomposition.  The key axis of one head is cut into sub-tiles of 32 rows.  A wavefront owns a sub-tile
-// from the memory request to the MFMAs: the 32 K rows (and V rows) go from HBM straight into the wavefront's
-// private slice of LDS (global_load_lds_dwordx4: no staging registers, no ds_write), 1 KB of consecutive bytes
-// per instruction, with an XOR swizzle applied on the global side so that the operand reads are conflict free.
-// Wavefronts never wait for each other inside the key loop; the four wavefronts of a workgroup meet once, at
-// the end, to merge their softmax states into one partial result per workgroup.  Loads of one wavefront overlap
-// with the MFMAs of the others (two workgroups = eight wavefronts per CU).
+// Work decomposition.  The key axis of one head is cut into sub-tiles of 32 rows, staged in LDS with an XOR
+// swizzle (applied on the global side of the load) so that the operand reads are conflict free.  How a workgroup
+// walks them depends on the launch (see sparse_attn_kernel): with at most 16 queries a wavefront owns a sub-tile
+// from the memory request to the MFMAs — in the sparse step the rows go from HBM straight into the wavefront's
+// private slice of LDS (global_load_lds_dwordx4: no staging registers, no ds_write), wavefronts never wait for each
+// other inside the key loop and meet once, at the end, to merge their softmax states; with more queries the
+// wavefronts take one 16-query tile each and share the staged sub-tiles.
 //
 // MFMA layout used (16x16x32, D[i][j] += sum_k A[i][k] B[k][j]; lane = 16*g + c):
 //   A operand: lane holds A[i = c][k = 8g .. 8g+7];  B operand: lane holds B[k = 8g .. 8g+7][j = c];

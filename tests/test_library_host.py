@@ -112,3 +112,13 @@ def test_bad_arguments_are_rejected_on_the_host(L):
                                fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_sparse_attn(fake, fake, None, 8, fake, fake, sp, fake, 4, fake, 2, fake, None, fake, 64, None) == fb.FOCUS_EWORKSPACE
     assert fb.last_error() != ""
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No silent fallback: without the built HIP library the binding raises, and so does everything on top of it."""
+    monkeypatch.setattr(fb, "_lib", None)
+    monkeypatch.setattr(fb, "LIB_PATH", str(tmp_path / "libfocus_hip.so"))
+    with pytest.raises(FileNotFoundError):
+        fb.lib()
+    with pytest.raises(FileNotFoundError):
+        fb.helper_k(4.0, 1)
