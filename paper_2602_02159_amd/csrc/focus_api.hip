@@ -56,7 +56,7 @@ static void plan_attention_splits(SplitPlan& p, const focus_shape& s) {
   if (p.q_tiles_per_group > 1) {
     plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 512));  // two resident workgroups per compute unit
   } else if (p.per_split > kWavesPerGroup && env_int("FOCUS_ATTN_PIPE", 1) == 1) {
-    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 512));
+    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 256));  // one resident workgroup per compute unit
     p.pipelined = p.per_split > kWavesPerGroup;
   }
 }
