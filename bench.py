@@ -386,11 +386,8 @@ def main() -> int:
         # block entry (Alg. 1): every position is active and attends to every key; 4 L^2 d H flops against the bf16 MFMA peak
         q_all = torch.randn(H, L, d, device=dev).to(torch.bfloat16)
         out_all = torch.empty(H, L, d, dtype=torch.bfloat16, device=dev)
-        act_all = torch.arange(L, dtype=torch.int32, device=dev)
-        blocks_all = torch.arange(n_b, dtype=torch.int32, device=dev)
         s_all = fb.make_shape(q_all, k0, v0, M, w.block, out_all)
-        ws_all = torch.empty(max(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s_all, L, n_b, 0), 256), dtype=torch.uint8, device=dev)
-        call = lambda: fb.sparse_attn(q_all, act_all, None, k0, v0, s_all, blocks_all, n_b, None, 0, out_all, None, ws_all)
+        call = lambda: fb.refresh_attn(q_all, k0, v0, s_all, out_all, None)
         call()
         sync()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -405,7 +402,7 @@ def main() -> int:
                                         "alg_flops": int(fl), "GBps": round(2 * 2 * L * H * d * 2 / us * 1e-3, 1),
                                         "TFLOPps": round(fl / us * 1e-6, 1), "mfma_frac": round(fl / us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
                                         "bound": "mfma"}
-        del q_all, out_all, ws_all
+        del q_all, out_all
 
     # the stage that takes the largest share of the timed step
     # (the step calls focus_sparse_layer; its parts are also timed through the separate entry points, which run the same kernels)

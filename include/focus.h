@@ -14,6 +14,7 @@
  *     focus_sparse_layer     = focus_block_scores + focus_sparse_attn of one layer, fused into fewer launches
  *     focus_probe_layer      = dense attention of the probe layer + focus_find_sinks, sharing the QK^T work
  *     focus_block_partials / focus_top_blocks   the two halves of focus_block_scores (head-sharded callers)
+ *     focus_refresh_attn     dense attention of every position (block entry)
  * and, around the step (Sec. 3):
  *     focus_token_confidence vocabulary logits -> predicted tokens, confidences (Eq. 2): the input of the selection
  *     focus_cache_update     new K/V states of the active positions -> KV cache (Eq. 3)
@@ -192,6 +193,17 @@ int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* a
 int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active,
                       const void* K, const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse,
                       float* col_mass, int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Block-entry refresh (Alg. 1: at a block entry I_active is every position and attention is not pruned): dense
+ * bidirectional attention of ALL n_gen rows of Q over all M + N keys,
+ *   out[h, i, :] = softmax_j(Q[h, i] . K[h, j] / sqrt(d)) . V[h, j, :],   i in [0, n_gen), j in [0, M + N).
+ *   out  [dev] bf16 [H, n_gen, d] with strides o_stride_*;  lse [dev] fp32 [H, n_gen] (natural log), may be NULL
+ * No index lists and no workspace.  The result equals focus_sparse_attn with every row active and every block kept,
+ * to rounding; this entry point is the one built for the compute-bound shape (thousands of queries).
+ */
+int focus_refresh_attn(const void* Q, const void* K, const void* V, const focus_shape* shape, void* out, float* lse,
+                       void* stream);
 
 /*
  * Predicted token and confidence of every position of the generation block (Sec. 3, Eq. 2): the input of Eq. 4.

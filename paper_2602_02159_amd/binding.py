@@ -19,7 +19,7 @@ FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0,
 FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER = 1, 2, 3, 4, 5
 
 EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
-           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer",
+           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn",
            "focus_token_confidence", "focus_token_confidence_workspace", "focus_cache_update",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
         L.focus_probe_layer.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, p, p, sz, p]
+        L.focus_refresh_attn.argtypes = [p, p, p, sp, p, p, p]
         L.focus_token_confidence.argtypes = [p, C.c_int64, p, i32, i32, p, p, p, sz, p]
         L.focus_token_confidence_workspace.argtypes = [i32, i32]
         L.focus_token_confidence_workspace.restype = sz
@@ -66,7 +67,7 @@ def lib() -> C.CDLL:
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
                      "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
-                     "focus_probe_layer", "focus_token_confidence", "focus_cache_update"):
+                     "focus_probe_layer", "focus_refresh_attn", "focus_token_confidence", "focus_cache_update"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
         L.focus_workspace_bytes.restype = sz
@@ -199,6 +200,13 @@ def probe_layer(q, active_idx, counts, k, v, shape: Shape, n_sink: int, out, lse
                                    C.byref(shape), n_sink, _ptr(out), _ptr(lse), _ptr(col_mass), _ptr(sink_idx),
                                    _ptr(workspace),
                                    0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def refresh_attn(q, k, v, shape: Shape, out, lse) -> None:
+    """Dense attention of every row of q over every row of k / v (block-entry refresh)."""
+    for t, name in ((q, "Q"), (k, "K"), (v, "V"), (out, "out")):
+        _need(t, torch.bfloat16, name)
+    _check(lib().focus_refresh_attn(_ptr(q), _ptr(k), _ptr(v), C.byref(shape), _ptr(out), _ptr(lse), _stream()))
 
 
 def token_confidence_workspace(n_rows: int, vocab: int) -> int:

@@ -375,6 +375,19 @@ size_t focus_token_confidence_workspace(int32_t n_rows, int32_t vocab) {
   return std::max<size_t>(token_confidence_workspace(n_rows, vocab), 16);
 }
 
+int focus_refresh_attn(const void* Q, const void* K, const void* V, const focus_shape* shape, void* out, float* lse,
+                       void* stream) {
+  if (int rc = check_shape(shape, true, true, true, true)) return rc;
+  if (!Q || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_refresh_attn: NULL pointer");
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out))
+    return fail(FOCUS_EINVAL, "focus_refresh_attn: pointers must be 16-byte aligned");
+  if (ceil_div(shape->n_gen, 128) > 0x7fffffff / 2 || shape->n_heads > 65535)
+    return fail(FOCUS_EUNSUPPORTED, "focus_refresh_attn: grid too large");
+  hipError_t e = launch_refresh_attn(Q, K, V, *shape, out, lse, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_refresh_attn", e);
+  return FOCUS_OK;
+}
+
 int focus_token_confidence(const void* logits, int64_t row_stride, const uint8_t* masked, int32_t n_rows, int32_t vocab,
                            int32_t* tokens, float* conf, void* workspace, size_t ws_bytes, void* stream) {
   if (!logits || !tokens || !conf) return fail(FOCUS_EINVAL, "focus_token_confidence: NULL pointer");

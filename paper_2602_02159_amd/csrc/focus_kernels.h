@@ -96,4 +96,8 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
                               float* lse, float* part_o, float* part_ml, const FusedTopC* fused, hipStream_t st,
                               const DenseProbe* probe = nullptr);
 
+// Block-entry refresh: dense attention of all n_gen rows of Q over all M + N keys (out [H, n_gen, d], lse [H, n_gen])
+hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, const focus_shape& s, void* out, float* lse,
+                               hipStream_t st);
+
 }  // namespace focus

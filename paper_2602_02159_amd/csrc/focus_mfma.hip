@@ -931,6 +931,148 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
 }
 
 // =====================================================================================================
+// Block-entry refresh (Alg. 1, I_active = all positions): dense bidirectional attention of EVERY row of Q over every
+// key — the one MFMA-bound launch of the method (4 n_q L d flops per head against 2 L d 2 bytes of K and V).
+// A workgroup holds 128 consecutive queries, 32 per wavefront (two 16-query tiles, so that every K and V^T operand read
+// from LDS feeds two MFMAs), and walks the key axis in 32-row sub-tiles shared by its four wavefronts and
+// double-buffered through registers: while sub-tile t is multiplied, sub-tile t + 1 sits in the second stage and the
+// rows of t + 2 are in flight.  No index lists, no key splits: each workgroup normalises and writes its own rows.
+// Grid (query blocks, heads), query blocks fastest: neighbouring workgroups share a head and find its K/V rows in L2.
+// =====================================================================================================
+struct RefreshArgs {
+  const uint16_t* Q;
+  const uint16_t* K;
+  const uint16_t* V;
+  uint16_t* out;
+  float* lse;  // [H, n_q] natural log, or null
+  int64_t qsh, qsn, ksh, ksn, vsh, vsn, osh, osn;
+  int n_q, L;
+  float scale_log2;
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs p) {
+  using G = Geo<D>;
+  constexpr int NQT = 2;                         // query tiles per wavefront
+  constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage of one sub-tile
+  constexpr int NL = G::kLoads / 2;              // loads per wavefront and sub-tile: half of the K or of the V rows
+  __shared__ __attribute__((aligned(16))) char stage[2][kBufBytes];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = lane & 15, g = lane >> 4;
+  const int h = blockIdx.y;
+  const int q_first = blockIdx.x * (kWavesPerGroup * NQT * kQTile) + wave * (NQT * kQTile);
+  const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
+  const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
+  const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
+  const int n_tiles = (p.L + kSubTile - 1) / kSubTile;
+
+  // this wavefront's share of every sub-tile: wavefronts 0, 1 the two halves of the K rows, 2, 3 of the V rows
+  const bool is_v = wave >= 2;
+  const int first = (wave & 1) * NL;
+  const uint16_t* src = is_v ? Vh : Kh;
+  const int64_t src_sn = is_v ? p.vsn : p.ksn;
+  uintx4 r[NL];
+  auto tile_of = [&](int t) {
+    SubTile s;
+    s.kind = 0;
+    s.row0 = t * kSubTile;
+    s.vmask = low_mask(min(p.L - s.row0, kSubTile));
+    return s;
+  };
+  auto fetch = [&](int t) { fetch_subtile_part<D, NL>(src, src_sn, tile_of(t), nullptr, 0, lane, first, r); };
+  auto store = [&](int t) { store_subtile_part<D, NL>(stage[t & 1] + (is_v ? G::kStageBytes : 0), lane, first, r); };
+
+  fetch(0);
+  bf16x8 q[NQT][G::kKSteps];
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) {
+    const int row = q_first + qt * kQTile + c;
+    load_q_tile<D>(q[qt], Qh, p.qsn, row < p.n_q ? row : -1, lane);
+  }
+  float m_run[NQT], l_run[NQT];
+  floatx4 o[NQT][G::kColTiles];
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) {
+    m_run[qt] = -INFINITY;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+  store(0);
+  if (1 < n_tiles) fetch(1);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();  // sub-tile t is staged; everyone is done with sub-tile t - 1
+    const char* sK = stage[t & 1];
+    const char* sV = sK + G::kStageBytes;
+    const uint32_t vmask = low_mask(min(p.L - t * kSubTile, kSubTile));
+    floatx4 acc[NQT][2];
+    qk_subtile<D, NQT>(acc, sK, q, lane);
+    bf16x8 pb[NQT];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+      float ps[8];
+      const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
+      if (t > 0 && __ballot(alpha != 1.f) != 0ull) {
+#pragma unroll
+        for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
+      }
+      pb[qt] = pack_bf16x8(ps);
+    }
+#pragma unroll
+    for (int ct = 0; ct < G::kColTiles; ++ct) {
+      const bf16x8 a = read_v_operand<D>(sV, ct, lane);
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
+    }
+    if (t + 1 < n_tiles) {
+      store(t + 1);  // requested a whole iteration ago; the stage was released by the barrier above
+      if (t + 2 < n_tiles) fetch(t + 2);
+    }
+  }
+  // lane (c, g) holds O^T[16 ct + 4 g + r][query c]: four consecutive output columns of one query per column tile
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) {
+    const int row = q_first + qt * kQTile + c;
+    if (row < p.n_q) {
+      const float inv = l_run[qt] > 0.f ? 1.f / l_run[qt] : 0.f;
+      uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)row * p.osn + 4 * g;
+#pragma unroll
+      for (int ct = 0; ct < G::kColTiles; ++ct) {
+        const floatx4 v = o[qt][ct];
+        *reinterpret_cast<uint2*>(dst + ct * 16) = make_uint2(cvt_pk_bf16(v[0] * inv, v[1] * inv), cvt_pk_bf16(v[2] * inv, v[3] * inv));
+      }
+      if (p.lse && g == 0)
+        p.lse[(int64_t)h * p.n_q + row] = l_run[qt] > 0.f ? (m_run[qt] + __builtin_amdgcn_logf(l_run[qt])) * kLn2 : -INFINITY;
+    }
+  }
+}
+
+hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, const focus_shape& s, void* out, float* lse,
+                               hipStream_t st) {
+  RefreshArgs a;
+  a.Q = static_cast<const uint16_t*>(Q);
+  a.K = static_cast<const uint16_t*>(K);
+  a.V = static_cast<const uint16_t*>(V);
+  a.out = static_cast<uint16_t*>(out);
+  a.lse = lse;
+  a.qsh = s.q_stride_h; a.qsn = s.q_stride_n;
+  a.ksh = s.k_stride_h; a.ksn = s.k_stride_n;
+  a.vsh = s.v_stride_h; a.vsn = s.v_stride_n;
+  a.osh = s.o_stride_h; a.osn = s.o_stride_n;
+  a.n_q = s.n_gen;
+  a.L = s.n_ctx + s.n_resp;
+  a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
+  const dim3 grid(ceil_div(s.n_gen, kWavesPerGroup * 2 * kQTile), s.n_heads);
+  if (s.head_dim == 128)
+    hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(refresh_attn_kernel<64>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// =====================================================================================================
 // Probe-layer logits (Eq. 6, first half): logits[h, j, q] = log2(e) * Q[h, i_q] . K[h, j] / sqrt(d) for every key
 // j in [0, L), and per (head, query, split) the maximum and the sum of exp2(logit - maximum).
 // =====================================================================================================

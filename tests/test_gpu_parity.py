@@ -509,6 +509,43 @@ def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
         assert all(torch.equal(a, b["out"]) for a, b in zip(eager, st.bufs))
 
 
+# ------------------------------------------------------------------------------------------------ block-entry refresh
+@pytest.mark.parametrize("H,M,N,d", [(4, 1024, 32, 64), (2, 2050, 33, 128), (3, 100, 7, 128), (1, 5, 0, 64), (2, 4096, 64, 128)])
+def test_refresh_attn_equals_full_bidirectional_attention(G, H, M, N, d):
+    """Every position attends to every position: against the oracle's dense reduction, an independent fp64
+    scaled_dot_product_attention, and focus_sparse_attn with everything kept."""
+    L = M + N
+    q, k, v = (_rand_bf16(101 + i, H, L, d).to(G.DEV) for i in range(3))
+    out = torch.full((H, L, d), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    lse = torch.full((H, L), float("nan"), dtype=torch.float32, device=G.DEV)
+    s = fb.make_shape(q, k, v, M, 64, out)
+    fb.refresh_attn(q, k, v, s, out, lse)
+    torch.cuda.synchronize()
+    Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
+    ref, ref_lse = fo.sparse_attention(Q, np.arange(L), K, V, np.arange(M), M)
+    G.assert_attention_close(out, ref)
+    assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
+    sdpa = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(Q), torch.from_numpy(K), torch.from_numpy(V))
+    G.assert_attention_close(out, sdpa.numpy())
+    n_b = -(-M // 64)
+    out2, lse2 = G.gpu_sparse_attn(q, G.i32(np.arange(L)), None, k, v, M, 64, G.i32(np.arange(n_b)), None)
+    assert np.allclose(G.to_np(out), G.to_np(out2), atol=4e-3) and np.allclose(lse.cpu().numpy(), lse2.cpu().numpy(), atol=1e-5)
+
+
+def test_refresh_attn_strided_output_and_fewer_queries_than_keys(G):
+    H, M, N, d, n_q = 2, 700, 20, 128, 333
+    q = _rand_bf16(111, n_q, H, d).to(G.DEV).permute(1, 0, 2)            # [L, H, d] storage
+    k, v = _rand_bf16(112, H, M + N, d).to(G.DEV), _rand_bf16(113, H, M + N, d).to(G.DEV)
+    buf = torch.full((H, n_q, 2 * d), 7.0, dtype=torch.bfloat16, device=G.DEV)
+    out = buf[:, :, :d]                                                    # row stride 2 d: the other half must stay untouched
+    s = fb.make_shape(q, k, v, M, 64, out)
+    fb.refresh_attn(q, k, v, s, out, None)
+    torch.cuda.synchronize()
+    ref, _ = fo.sparse_attention(G.to_np(q), np.arange(n_q), G.to_np(k), G.to_np(v), np.arange(M), M)
+    G.assert_attention_close(out, ref)
+    assert (buf[:, :, d:] == 7.0).all()
+
+
 # ------------------------------------------------------------------------------------------------ around the step
 @pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
 def test_token_confidence(G, n_rows, vocab, pad):

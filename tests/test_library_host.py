@@ -97,6 +97,9 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert fb.token_confidence_workspace(64, 131072) >= 64 * 16 * 12 and fb.token_confidence_workspace(0, 10) == 0
     assert L.focus_cache_update(fake, None, sp, fake, fake, 512, 64, fake, None, 8, 1024, None) == fb.FOCUS_EINVAL
     assert L.focus_cache_update(fake, fake, sp, fake, fake, 512, 60, fake, None, 8, 1024, None) == fb.FOCUS_EINVAL
+    # refresh: NULL output, misaligned K
+    assert L.focus_refresh_attn(fake, fake, fake, sp, None, None, None) == fb.FOCUS_EINVAL
+    assert L.focus_refresh_attn(fake, C.c_void_p(4104), fake, sp, fake, None, None) == fb.FOCUS_EINVAL
     # probe layer: NULL V, n_sink out of range, workspace too small
     assert L.focus_probe_layer(fake, fake, None, 8, fake, None, sp, 2, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_probe_layer(fake, fake, None, 8, fake, fake, sp, 5000, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
