@@ -383,6 +383,8 @@ int focus_refresh_attn(const void* Q, const void* K, const void* V, const focus_
     return fail(FOCUS_EINVAL, "focus_refresh_attn: pointers must be 16-byte aligned");
   if (ceil_div(shape->n_gen, 128) > 0x7fffffff / 2 || shape->n_heads > 65535)
     return fail(FOCUS_EUNSUPPORTED, "focus_refresh_attn: grid too large");
+  if (shape->k_stride_n >= (1 << 25) || shape->v_stride_n >= (1 << 25))  // 32-row byte offsets are kept in 32 bits
+    return fail(FOCUS_EUNSUPPORTED, "focus_refresh_attn: K/V row stride must be below 2^25 elements");
   hipError_t e = launch_refresh_attn(Q, K, V, *shape, out, lse, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return launch_fail("focus_refresh_attn", e);
   return FOCUS_OK;

@@ -24,6 +24,7 @@
 // where the contraction slot (g, e) stands for key 16*(e/4) + 4g + (e%4) of the sub-tile on both operands.
 // The V^T operand is read from the row-major staged tile with the transposing LDS read ds_read_b64_tr_b16.
 #include <cstdlib>
+#include <type_traits>
 
 #include "focus_common.h"
 #include "focus_kernels.h"
@@ -933,10 +934,18 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
 // =====================================================================================================
 // Block-entry refresh (Alg. 1, I_active = all positions): dense bidirectional attention of EVERY row of Q over every
 // key — the one MFMA-bound launch of the method (4 n_q L d flops per head against 2 L d 2 bytes of K and V).
-// A workgroup holds 128 consecutive queries, 32 per wavefront (two 16-query tiles, so that every K and V^T operand read
-// from LDS feeds two MFMAs), and walks the key axis in 32-row sub-tiles shared by its four wavefronts and
-// double-buffered through registers: while sub-tile t is multiplied, sub-tile t + 1 sits in the second stage and the
-// rows of t + 2 are in flight.  No index lists, no key splits: each workgroup normalises and writes its own rows.
+// A workgroup holds 128 consecutive queries, 32 per wavefront, and walks the key axis in 32-row sub-tiles shared by
+// its four wavefronts and double-buffered through registers: while sub-tile t is multiplied, sub-tile t + 1 sits in
+// the second stage and the rows of t + 2 are in flight.  Both products use the 32x32x16 MFMA:
+//   S^T = K Q^T   lane (query = lane % 32, hh = lane / 32) register v holds the logit of key 8 (v / 4) + 4 hh + v % 4,
+//                 so a query's 32 logits sit in two lanes and the row maximum costs one cross-lane exchange;
+//   O^T = V^T P^T the same registers, packed to bf16 eight at a time, are the B operand of k-step s = v / 8; the A
+//                 operand is read transposed from the row-major staged V with the key slots in that same order.
+// The loop is bound by the vector ALU (exp2 and the multiply-adds around it), so everything else is kept out of it:
+// row addresses are one scalar base per sub-tile plus per-lane offsets computed once, the running sum is taken by
+// v_dot2 over the packed bf16 pairs (two values per instruction, and the very values that enter the PV product),
+// the rescale of O runs only when some running maximum in the wavefront moved, and the ragged last sub-tile has a
+// loop body of its own.  No index lists, no key splits: each workgroup normalises and writes its own rows.
 // Grid (query blocks, heads), query blocks fastest: neighbouring workgroups share a head and find its K/V rows in L2.
 // =====================================================================================================
 struct RefreshArgs {
@@ -950,102 +959,188 @@ struct RefreshArgs {
   float scale_log2;
 };
 
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int kRefreshQueries = 128;  // queries per workgroup of the refresh kernel
+
+// A operand of O^T += V^T P^T (32x32x16) for d tile `dt` and k-step `ks`: lane (dcol = lane % 32, hh) needs
+// V[16 ks + 8 (e / 4) + 4 hh + e % 4][32 dt + dcol], e = 0..7 — two transposed reads of four consecutive rows each.
+// The staged V of this kernel is only ever read this way — one instruction touches eight rows (four per half of the
+// wavefront) and 64 bytes of each — so its rows are swizzled for that: rows that would fall on the same banks
+// (consecutive rows at d = 128, every other row at d = 64) get different 64-byte segments.
+template <int D>
+__device__ __forceinline__ int vstage_swz(int row) {
+  return D == 128 ? (row & 3) << 2 : ((row >> 1) & 1) << 2;
+}
+template <int D>
+__device__ __forceinline__ int vstage_off(int row, int chunk) {
+  return row * Geo<D>::kRowBytes + ((chunk ^ vstage_swz<D>(row)) << 4);
+}
+template <int D>
+__device__ __forceinline__ bf16x8 read_v_operand32(const char* stageV, int dt, int ks, int lane) {
+  const int s = lane & 15, b = lane >> 4;
+  const int row = 16 * ks + 4 * (b >> 1) + (s >> 2);
+  const int col = 32 * dt + 16 * (b & 1) + 4 * (s & 3);
+  const int off0 = vstage_off<D>(row, col >> 3) + (col & 7) * 2;
+  const int off1 = vstage_off<D>(row + 8, col >> 3) + (col & 7) * 2;
+  typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
+  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stageV + off0));
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stageV + off1));
+  struct { shortx4 a, b; } both = {lo, hi};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs p) {
   using G = Geo<D>;
-  constexpr int NQT = 2;                         // query tiles per wavefront
+  constexpr int kKS = D / 16;                    // k-steps of K Q^T
+  constexpr int kDT = D / 32;                    // 32-wide d tiles of V^T P^T
   constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage of one sub-tile
   constexpr int NL = G::kLoads / 2;              // loads per wavefront and sub-tile: half of the K or of the V rows
   __shared__ __attribute__((aligned(16))) char stage[2][kBufBytes];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int c = lane & 15, g = lane >> 4;
+  const int qi = lane & 31, hh = lane >> 5;
   const int h = blockIdx.y;
-  const int q_first = blockIdx.x * (kWavesPerGroup * NQT * kQTile) + wave * (NQT * kQTile);
-  const uint16_t* Qh = p.Q + (int64_t)h * p.qsh;
-  const uint16_t* Kh = p.K + (int64_t)h * p.ksh;
-  const uint16_t* Vh = p.V + (int64_t)h * p.vsh;
+  const int q_row = blockIdx.x * kRefreshQueries + wave * 32 + qi;
   const int n_tiles = (p.L + kSubTile - 1) / kSubTile;
+  const int n_full = p.L / kSubTile;
 
-  // this wavefront's share of every sub-tile: wavefronts 0, 1 the two halves of the K rows, 2, 3 of the V rows
+  // this wavefront's share of every sub-tile: wavefronts 0, 1 the two halves of the K rows, 2, 3 of the V rows.
+  // Row addresses: a scalar base that moves by 32 rows per sub-tile plus per-lane byte offsets fixed for the launch.
   const bool is_v = wave >= 2;
   const int first = (wave & 1) * NL;
-  const uint16_t* src = is_v ? Vh : Kh;
-  const int64_t src_sn = is_v ? p.vsn : p.ksn;
+  const char* src = reinterpret_cast<const char*>(is_v ? p.V + (int64_t)h * p.vsh : p.K + (int64_t)h * p.ksh);
+  const int64_t row_bytes = (is_v ? p.vsn : p.ksn) * 2;
+  const int64_t tile_bytes = row_bytes * kSubTile;
+  auto swz = [&](int slot) { return is_v ? vstage_swz<D>(slot) : (slot & (G::kChunks - 1)); };  // chunk permutation of a staged row
+  uint32_t voff[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int slot = (first + i) * G::kRowsPerLoad + lane / G::kChunks;
+    voff[i] = (uint32_t)slot * (uint32_t)row_bytes + (((lane % G::kChunks) ^ swz(slot)) << 4);
+  }
   uintx4 r[NL];
-  auto tile_of = [&](int t) {
-    SubTile s;
-    s.kind = 0;
-    s.row0 = t * kSubTile;
-    s.vmask = low_mask(min(p.L - s.row0, kSubTile));
-    return s;
+  auto fetch = [&](int t) {
+    const char* base = src + (int64_t)t * tile_bytes;
+    if (t >= n_full) {  // the ragged last sub-tile: slots past the end read its last row instead (masked below)
+      const int last = p.L - t * kSubTile - 1;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int slot = (first + i) * G::kRowsPerLoad + lane / G::kChunks;
+        voff[i] = (uint32_t)min(slot, last) * (uint32_t)row_bytes + (((lane % G::kChunks) ^ swz(slot)) << 4);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + voff[i]));
   };
-  auto fetch = [&](int t) { fetch_subtile_part<D, NL>(src, src_sn, tile_of(t), nullptr, 0, lane, first, r); };
-  auto store = [&](int t) { store_subtile_part<D, NL>(stage[t & 1] + (is_v ? G::kStageBytes : 0), lane, first, r); };
+  // stage index as a compile-time constant where the loop is unrolled by two (every LDS address is then a register
+  // fixed for the launch plus an immediate); -1: taken from the sub-tile number at run time
+  char* my_stage = stage[0] + (is_v ? G::kStageBytes : 0) + first * 1024 + lane * 16;
+  auto store = [&](int t, auto which) {
+    constexpr int W = decltype(which)::value;
+    const int off = (W >= 0 ? W : (t & 1)) * kBufBytes;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) *reinterpret_cast<uintx4*>(my_stage + off + i * 1024) = r[i];
+  };
 
   fetch(0);
-  bf16x8 q[NQT][G::kKSteps];
+  bf16x8 q[kKS];  // B operand of K Q^T: lane (query, hh) holds Q[query][16 ks + 8 hh .. + 7]
+  {
+    const uint16_t* qsrc = p.Q + (int64_t)h * p.qsh + (int64_t)min(q_row, p.n_q - 1) * p.qsn + hh * 8;
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int row = q_first + qt * kQTile + c;
-    load_q_tile<D>(q[qt], Qh, p.qsn, row < p.n_q ? row : -1, lane);
+    for (int ks = 0; ks < kKS; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(qsrc + ks * 16);
+      q[ks] = as_bf16x8(q_row < p.n_q ? v : make_uint4(0u, 0u, 0u, 0u));
+    }
   }
-  float m_run[NQT], l_run[NQT];
-  floatx4 o[NQT][G::kColTiles];
+  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's share of the row sum (its 16 of every 32 keys)
+  floatx16 o[kDT];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    m_run[qt] = -INFINITY;
-    l_run[qt] = 0.f;
+  for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-    for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
-  }
-  store(0);
+    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  store(0, std::integral_constant<int, 0>{});
   if (1 < n_tiles) fetch(1);
-  for (int t = 0; t < n_tiles; ++t) {
+
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  auto body = [&](int t, auto ragged, auto which) {
+    constexpr int W = decltype(which)::value;
     __syncthreads();  // sub-tile t is staged; everyone is done with sub-tile t - 1
-    const char* sK = stage[t & 1];
+    const char* sK = stage[W >= 0 ? W : (t & 1)];
     const char* sV = sK + G::kStageBytes;
-    const uint32_t vmask = low_mask(min(p.L - t * kSubTile, kSubTile));
-    floatx4 acc[NQT][2];
-    qk_subtile<D, NQT>(acc, sK, q, lane);
-    bf16x8 pb[NQT];
+    floatx16 acc;
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      float ps[8];
-      const float alpha = softmax_step(acc[qt], vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
-      if (t > 0 && __ballot(alpha != 1.f) != 0ull) {
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-        for (int ct = 0; ct < G::kColTiles; ++ct) o[qt][ct] *= alpha;
-      }
-      pb[qt] = pack_bf16x8(ps);
+    for (int ks = 0; ks < kKS; ++ks) {
+      const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(sK + stage_off<D>(qi, 2 * ks + hh)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[ks], acc, 0, 0, 0);
+    }
+    if (decltype(ragged)::value) {
+      const int n_valid = p.L - t * kSubTile;
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (8 * (v >> 2) + 4 * hh + (v & 3) >= n_valid) acc[v] = -INFINITY;
+    }
+    float mx = fmaxf(acc[0], acc[1]);
+#pragma unroll
+    for (int v = 2; v < 16; ++v) mx = fmaxf(mx, acc[v]);
+    {
+      const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
+    }
+    if (__ballot(mx > m_run) != 0ull) {  // some running maximum of this wavefront moves: rescale (rare after the first sub-tiles)
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first sub-tile (m_run = -inf, m_new finite)
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < kDT; ++dt) o[dt] *= alpha;
+    }
+    uint32_t pk[8];
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], p.scale_log2, -m_run));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v + 1], p.scale_log2, -m_run));
+      pk[v >> 1] = cvt_pk_bf16(p0, p1);
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v >> 1]), ones, l_run, false);
     }
 #pragma unroll
-    for (int ct = 0; ct < G::kColTiles; ++ct) {
-      const bf16x8 a = read_v_operand<D>(sV, ct, lane);
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8 pb = as_bf16x8(make_uint4(pk[4 * ks], pk[4 * ks + 1], pk[4 * ks + 2], pk[4 * ks + 3]));
 #pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) o[qt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qt], o[qt][ct], 0, 0, 0);
+      for (int dt = 0; dt < kDT; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand32<D>(sV, dt, ks, lane), pb, o[dt], 0, 0, 0);
     }
     if (t + 1 < n_tiles) {
-      store(t + 1);  // requested a whole iteration ago; the stage was released by the barrier above
+      store(t + 1, std::integral_constant<int, (W >= 0 ? 1 - W : -1)>{});  // requested a whole iteration ago; the stage was released by the barrier above
       if (t + 2 < n_tiles) fetch(t + 2);
     }
+  };
+  for (int t = 0; t < n_full; t += 2) {
+    body(t, std::false_type{}, std::integral_constant<int, 0>{});
+    if (t + 1 < n_full) body(t + 1, std::false_type{}, std::integral_constant<int, 1>{});
   }
-  // lane (c, g) holds O^T[16 ct + 4 g + r][query c]: four consecutive output columns of one query per column tile
+  if (n_full < n_tiles) body(n_full, std::true_type{}, std::integral_constant<int, -1>{});
+
+  // lane (query, hh) register v of d tile dt holds O^T[32 dt + 8 (v / 4) + 4 hh + v % 4][query]: four consecutive
+  // output columns per register quad.  The two lanes of a query add their halves of the row sum.
+  {
+    const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+    l_run = __uint_as_float(sw.x) + __uint_as_float(sw.y);
+  }
+  if (q_row < p.n_q) {
+    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+    uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)q_row * p.osn + 4 * hh;
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int row = q_first + qt * kQTile + c;
-    if (row < p.n_q) {
-      const float inv = l_run[qt] > 0.f ? 1.f / l_run[qt] : 0.f;
-      uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)row * p.osn + 4 * g;
+    for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-      for (int ct = 0; ct < G::kColTiles; ++ct) {
-        const floatx4 v = o[qt][ct];
-        *reinterpret_cast<uint2*>(dst + ct * 16) = make_uint2(cvt_pk_bf16(v[0] * inv, v[1] * inv), cvt_pk_bf16(v[2] * inv, v[3] * inv));
-      }
-      if (p.lse && g == 0)
-        p.lse[(int64_t)h * p.n_q + row] = l_run[qt] > 0.f ? (m_run[qt] + __builtin_amdgcn_logf(l_run[qt])) * kLn2 : -INFINITY;
-    }
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<uint2*>(dst + 32 * dt + 8 * j) =
+            make_uint2(cvt_pk_bf16(o[dt][4 * j] * inv, o[dt][4 * j + 1] * inv), cvt_pk_bf16(o[dt][4 * j + 2] * inv, o[dt][4 * j + 3] * inv));
+    if (p.lse && hh == 0)
+      p.lse[(int64_t)h * p.n_q + q_row] = l_run > 0.f ? (m_run + __builtin_amdgcn_logf(l_run)) * kLn2 : -INFINITY;
   }
 }
 
@@ -1064,7 +1159,7 @@ hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, cons
   a.n_q = s.n_gen;
   a.L = s.n_ctx + s.n_resp;
   a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
-  const dim3 grid(ceil_div(s.n_gen, kWavesPerGroup * 2 * kQTile), s.n_heads);
+  const dim3 grid(ceil_div(s.n_gen, kRefreshQueries), s.n_heads);
   if (s.head_dim == 128)
     hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(256), 0, st, a);
   else

@@ -529,7 +529,9 @@ def test_refresh_attn_equals_full_bidirectional_attention(G, H, M, N, d):
     G.assert_attention_close(out, sdpa.numpy())
     n_b = -(-M // 64)
     out2, lse2 = G.gpu_sparse_attn(q, G.i32(np.arange(L)), None, k, v, M, 64, G.i32(np.arange(n_b)), None)
-    assert np.allclose(G.to_np(out), G.to_np(out2), atol=4e-3) and np.allclose(lse.cpu().numpy(), lse2.cpu().numpy(), atol=1e-5)
+    # the two kernels round differently (this one sums the bf16-rounded probabilities): close, not identical
+    G.assert_attention_close(out, G.to_np(out2))
+    assert np.allclose(lse.cpu().numpy(), lse2.cpu().numpy(), atol=1e-3)
 
 
 def test_refresh_attn_strided_output_and_fewer_queries_than_keys(G):
