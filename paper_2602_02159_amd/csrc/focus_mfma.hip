@@ -25,6 +25,7 @@
 // The V^T operand is read from the row-major staged tile with the transposing LDS read ds_read_b64_tr_b16.
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 #include "focus_common.h"
 #include "focus_kernels.h"
@@ -960,6 +961,15 @@ struct RefreshArgs {
 };
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant expression
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 constexpr int kRefreshQueries = 128;  // queries per workgroup of the refresh kernel
 
 // A operand of O^T += V^T P^T (32x32x16) for d tile `dt` and k-step `ks`: lane (dcol = lane % 32, hh) needs
@@ -1034,16 +1044,24 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
 #pragma unroll
     for (int i = 0; i < NL; ++i) r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + voff[i]));
   };
-  // stage index as a compile-time constant where the loop is unrolled by two (every LDS address is then a register
-  // fixed for the launch plus an immediate); -1: taken from the sub-tile number at run time
+  // K runs one sub-tile ahead of V: iteration t multiplies K sub-tile t + 1 (the logits of the NEXT iteration, MFMA
+  // work with nothing in front of it) while the vector ALU turns the logits of sub-tile t into probabilities, then
+  // multiplies those with V sub-tile t.  K sub-tile j lives in K stage j % 2, V sub-tile j in V stage j % 2.
+  // The loop is unrolled by two so that every stage index is a compile-time constant (an LDS address is then a
+  // register fixed for the launch plus an immediate); -1: taken from the sub-tile number at run time.
+  const int lead = is_v ? 0 : 1;
   char* my_stage = stage[0] + (is_v ? G::kStageBytes : 0) + first * 1024 + lane * 16;
-  auto store = [&](int t, auto which) {
-    constexpr int W = decltype(which)::value;
-    const int off = (W >= 0 ? W : (t & 1)) * kBufBytes;
+  auto store = [&](int j) {  // this wavefront's rows of sub-tile j (in r) to stage j % 2
 #pragma unroll
-    for (int i = 0; i < NL; ++i) *reinterpret_cast<uintx4*>(my_stage + off + i * 1024) = r[i];
+    for (int i = 0; i < NL; ++i) *reinterpret_cast<uintx4*>(my_stage + (j & 1) * kBufBytes + i * 1024) = r[i];
   };
-
+  auto stage_next = [&](int t) {  // after the barrier of iteration t: K sub-tile t + 2 / V sub-tile t + 1, then request the one after
+    const int j = t + 1 + lead;
+    if (j < n_tiles) {
+      store(j);
+      if (j + 1 < n_tiles) fetch(j + 1);
+    }
+  };
   fetch(0);
   bf16x8 q[kKS];  // B operand of K Q^T: lane (query, hh) holds Q[query][16 ks + 8 hh .. + 7]
   {
@@ -1054,21 +1072,7 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
       q[ks] = as_bf16x8(q_row < p.n_q ? v : make_uint4(0u, 0u, 0u, 0u));
     }
   }
-  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's share of the row sum (its 16 of every 32 keys)
-  floatx16 o[kDT];
-#pragma unroll
-  for (int dt = 0; dt < kDT; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
-  store(0, std::integral_constant<int, 0>{});
-  if (1 < n_tiles) fetch(1);
-
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  auto body = [&](int t, auto ragged, auto which) {
-    constexpr int W = decltype(which)::value;
-    __syncthreads();  // sub-tile t is staged; everyone is done with sub-tile t - 1
-    const char* sK = stage[W >= 0 ? W : (t & 1)];
-    const char* sV = sK + G::kStageBytes;
+  auto qk = [&](const char* sK) {
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -1077,20 +1081,26 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
       const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(sK + stage_off<D>(qi, 2 * ks + hh)));
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[ks], acc, 0, 0, 0);
     }
-    if (decltype(ragged)::value) {
-      const int n_valid = p.L - t * kSubTile;
+    return acc;
+  };
+  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's share of the row sum (its 16 of every 32 keys)
+  floatx16 o[kDT];
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (8 * (v >> 2) + 4 * hh + (v & 3) >= n_valid) acc[v] = -INFINITY;
-    }
-    float mx = fmaxf(acc[0], acc[1]);
+  for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-    for (int v = 2; v < 16; ++v) mx = fmaxf(mx, acc[v]);
-    {
-      const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-      mx = fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
-    }
-    if (__ballot(mx > m_run) != 0ull) {  // some running maximum of this wavefront moves: rescale (rare after the first sub-tiles)
+    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  // scaled row maximum of one sub-tile's logits.  Slots past the end of a ragged sub-tile hold copies of its last
+  // row, so they cannot raise the maximum and need no masking here.
+  auto row_max = [&](const floatx16& a) {
+    float mx = fmaxf(a[0], a[1]);
+#pragma unroll
+    for (int v = 2; v < 16; ++v) mx = fmaxf(mx, a[v]);
+    const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    return fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
+  };
+  auto rescale = [&](float mx) {
+    if (__ballot(mx > m_run) != 0ull) {  // some running maximum of this wavefront moves (rare after the first sub-tiles)
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first sub-tile (m_run = -inf, m_new finite)
       m_run = m_new;
@@ -1098,14 +1108,23 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
 #pragma unroll
       for (int dt = 0; dt < kDT; ++dt) o[dt] *= alpha;
     }
-    uint32_t pk[8];
+  };
+  // logits -> packed bf16 probabilities of the first n_valid key slots (0 for the rest); adds them to the running sum
+  auto probabilities = [&](const floatx16& a, uint32_t (&pk)[8], int n_valid) {
 #pragma unroll
     for (int v = 0; v < 16; v += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], p.scale_log2, -m_run));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v + 1], p.scale_log2, -m_run));
+      float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[v], p.scale_log2, -m_run));
+      float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[v + 1], p.scale_log2, -m_run));
+      if (n_valid < kSubTile) {
+        const int key = 8 * (v >> 2) + 4 * hh + (v & 3);
+        p0 = key < n_valid ? p0 : 0.f;
+        p1 = key + 1 < n_valid ? p1 : 0.f;
+      }
       pk[v >> 1] = cvt_pk_bf16(p0, p1);
       l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v >> 1]), ones, l_run, false);
     }
+  };
+  auto pv = [&](const char* sV, const uint32_t (&pk)[8]) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const bf16x8 pb = as_bf16x8(make_uint4(pk[4 * ks], pk[4 * ks + 1], pk[4 * ks + 2], pk[4 * ks + 3]));
@@ -1113,16 +1132,93 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
       for (int dt = 0; dt < kDT; ++dt)
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand32<D>(sV, dt, ks, lane), pb, o[dt], 0, 0, 0);
     }
-    if (t + 1 < n_tiles) {
-      store(t + 1, std::integral_constant<int, (W >= 0 ? 1 - W : -1)>{});  // requested a whole iteration ago; the stage was released by the barrier above
-      if (t + 2 < n_tiles) fetch(t + 2);
-    }
   };
-  for (int t = 0; t < n_full; t += 2) {
-    body(t, std::false_type{}, std::integral_constant<int, 0>{});
-    if (t + 1 < n_full) body(t + 1, std::false_type{}, std::integral_constant<int, 1>{});
+
+  // prologue: K sub-tile 0 staged and multiplied; K sub-tile 1 and V sub-tile 0 staged for iteration 0
+  if (!is_v) {
+    store(0);
+    if (1 < n_tiles) fetch(1);
   }
-  if (n_full < n_tiles) body(n_full, std::true_type{}, std::integral_constant<int, -1>{});
+  __syncthreads();
+  floatx16 acc = qk(stage[0]);
+  float mx = row_max(acc);
+  stage_next(-1);
+
+  // One iteration, written as NS slots of one MFMA each — K Q^T of sub-tile t + 1 first, then V^T P^T of sub-tile t —
+  // with scheduling fences between the slots: a wavefront issues in order, so the vector work of the other sub-tile
+  // (exponentials of sub-tile t beside the K Q^T MFMAs, the row maximum of sub-tile t + 1 beside the last V^T P^T
+  // MFMAs) has to sit between the MFMAs in program order or it would wait behind all of them.  The LDS operand of slot
+  // s + kLead is requested in slot s.
+  auto body = [&](int t, auto which) {  // t + 1 < n_tiles: sub-tile t is full
+    constexpr int W = decltype(which)::value;
+    constexpr int NS = kKS + 2 * kDT;  // MFMAs per iteration
+    constexpr int kLead = 3;
+    constexpr int kPer = 16 / kKS;     // logits turned into probabilities per K Q^T slot
+    __syncthreads();  // K sub-tile t + 1 and V sub-tile t are staged; everyone is done with iteration t - 1
+    rescale(mx);
+    const char* sK = stage[1 - W];
+    const char* sV = stage[W] + G::kStageBytes;
+    bf16x8 op[NS];
+    auto read_op = [&](auto sc) {
+      constexpr int s = decltype(sc)::value;
+      if constexpr (s < kKS)
+        op[s] = as_bf16x8(*reinterpret_cast<const uint4*>(sK + stage_off<D>(qi, 2 * s + hh)));
+      else
+        op[s] = read_v_operand32<D>(sV, (s - kKS) % kDT, (s - kKS) / kDT, lane);
+    };
+    floatx16 next;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) next[v] = 0.f;
+    uint32_t pk[8];
+    float mxn = 0.f;
+    static_for<kLead>(read_op);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NS>([&](auto sc) {
+      constexpr int s = decltype(sc)::value;
+      if constexpr (s + kLead < NS) read_op(std::integral_constant<int, s + kLead>{});
+      if constexpr (s < kKS) {
+        next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], q[s], next, 0, 0, 0);
+#pragma unroll
+        for (int v = s * kPer; v < (s + 1) * kPer; v += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], p.scale_log2, -m_run));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v + 1], p.scale_log2, -m_run));
+          pk[v >> 1] = cvt_pk_bf16(p0, p1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v >> 1]), ones, l_run, false);
+        }
+      } else {
+        constexpr int ks = (s - kKS) / kDT, dt = (s - kKS) % kDT;
+        const bf16x8 pb = as_bf16x8(make_uint4(pk[4 * ks], pk[4 * ks + 1], pk[4 * ks + 2], pk[4 * ks + 3]));
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], pb, o[dt], 0, 0, 0);
+        if constexpr (s == NS - 2) {  // row maximum of sub-tile t + 1: the in-lane part
+          mxn = fmaxf(next[0], next[1]);
+#pragma unroll
+          for (int v = 2; v < 16; ++v) mxn = fmaxf(mxn, next[v]);
+        }
+        if constexpr (s == NS - 1) {  // ... and the exchange between the two lanes of a query
+          const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mxn), __float_as_uint(mxn), false, false);
+          mxn = fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    mx = mxn;
+    stage_next(t);
+    acc = next;
+  };
+  int t_body = 0;
+  for (; t_body + 2 < n_tiles; t_body += 2) {  // straight-line pairs: no exit between the two halves
+    body(t_body, std::integral_constant<int, 0>{});
+    body(t_body + 1, std::integral_constant<int, 1>{});
+  }
+  if (t_body + 1 < n_tiles) body(t_body, std::integral_constant<int, 0>{});  // t_body is even
+  {  // last sub-tile (possibly ragged): its logits are in acc already
+    const int t = n_tiles - 1;
+    __syncthreads();
+    rescale(mx);
+    uint32_t pk[8];
+    probabilities(acc, pk, p.L - t * kSubTile);
+    pv(stage[t & 1] + G::kStageBytes, pk);
+  }
 
   // lane (query, hh) register v of d tile dt holds O^T[32 dt + 8 (v / 4) + 4 hh + v % 4][query]: four consecutive
   // output columns per register quad.  The two lanes of a query add their halves of the row sum.
