@@ -381,7 +381,13 @@ def main() -> int:
     ub = 2 * 2 * n_q * H * d * 2
     stages["cache_update"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": ub, "alg_flops": 0,
                               "GBps": round(ub / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(ub / us * 1e-3 / HBM_PEAK_GBS, 4)}
-    del vl, k_cache, v_cache
+    # block entry: every cache row rewritten, block means from the same pass (reads K, V; writes K, V, K_bar)
+    kbar_r = torch.empty(H, n_b, d, dtype=torch.float32, device=dev)
+    us = time_call(lambda: fb.cache_refresh(k_cache, v_cache, s_cache, k0, v0, kbar_r))
+    ub = 2 * 2 * L * H * d * 2 + H * n_b * d * 4
+    stages["cache_refresh"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": ub, "alg_flops": 0,
+                               "GBps": round(ub / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(ub / us * 1e-3 / HBM_PEAK_GBS, 4)}
+    del vl, k_cache, v_cache, kbar_r
     if args.full_refresh:
         # block entry (Alg. 1): every position is active and attends to every key; 4 L^2 d H flops against the bf16 MFMA peak
         q_all = torch.randn(H, L, d, device=dev).to(torch.bfloat16)

@@ -18,6 +18,7 @@
  * and, around the step (Sec. 3):
  *     focus_token_confidence vocabulary logits -> predicted tokens, confidences (Eq. 2): the input of the selection
  *     focus_cache_update     new K/V states of the active positions -> KV cache (Eq. 3)
+ *     focus_cache_refresh    block entry: new K/V states of every position -> KV cache and K_bar in one pass
  *
  * Conventions shared by every entry point
  *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
@@ -235,6 +236,18 @@ size_t focus_token_confidence_workspace(int32_t n_rows, int32_t vocab);
 int focus_cache_update(void* K_cache, void* V_cache, const focus_shape* shape, const void* K_new, const void* V_new,
                        int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
                        int32_t max_active, int32_t row_base, void* stream);
+
+/*
+ * Block-entry cache refresh (Alg. 1: when a generation block starts, every position is recomputed and the whole KV
+ * cache rewritten): all M + N cache rows take the new states, and the representative keys K_bar of the prompt blocks
+ * (Sec. 5.3) are formed in the same pass, so the new K is read once.
+ *   K_cache, V_cache [dev] bf16 [H, M+N, d], strides k_/v_stride_* of `shape`, overwritten
+ *   K_new, V_new     [dev] bf16 [H, M+N, d] with strides new_stride_h / new_stride_n (elements, multiples of 8); must
+ *                    not alias the caches
+ *   kbar             [dev] fp32 [H, n_b, d] out, or NULL (copy only).  Bit-identical to focus_block_means of the new K.
+ */
+int focus_cache_refresh(void* K_cache, void* V_cache, const focus_shape* shape, const void* K_new, const void* V_new,
+                        int64_t new_stride_h, int64_t new_stride_n, float* kbar, void* stream);
 
 /* Bytes of workspace `fn` needs for this shape; 0 on invalid arguments.  [host] only. */
 size_t focus_workspace_bytes(int32_t fn, const focus_shape* shape, int32_t max_active, int32_t n_keep,

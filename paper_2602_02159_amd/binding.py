@@ -19,7 +19,7 @@ FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0,
 FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER = 1, 2, 3, 4, 5
 
 EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
-           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn",
+           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn", "focus_cache_refresh",
            "focus_token_confidence", "focus_token_confidence_workspace", "focus_cache_update",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
         L.focus_probe_layer.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, p, p, sz, p]
         L.focus_refresh_attn.argtypes = [p, p, p, sp, p, p, p]
+        L.focus_cache_refresh.argtypes = [p, p, sp, p, p, C.c_int64, C.c_int64, p, p]
         L.focus_token_confidence.argtypes = [p, C.c_int64, p, i32, i32, p, p, p, sz, p]
         L.focus_token_confidence_workspace.argtypes = [i32, i32]
         L.focus_token_confidence_workspace.restype = sz
@@ -67,7 +68,7 @@ def lib() -> C.CDLL:
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
                      "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
-                     "focus_probe_layer", "focus_refresh_attn", "focus_token_confidence", "focus_cache_update"):
+                     "focus_probe_layer", "focus_refresh_attn", "focus_token_confidence", "focus_cache_update", "focus_cache_refresh"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
         L.focus_workspace_bytes.restype = sz
@@ -232,6 +233,18 @@ def cache_update(k_cache, v_cache, shape: Shape, k_new, v_new, active_idx, count
         raise ValueError("K_new and V_new must share their strides, innermost 1")
     _check(lib().focus_cache_update(_ptr(k_cache), _ptr(v_cache), C.byref(shape), _ptr(k_new), _ptr(v_new), k_new.stride(0),
                                     k_new.stride(1), _ptr(active_idx), _ptr(counts), active_idx.numel(), row_base, _stream()))
+
+
+def cache_refresh(k_cache, v_cache, shape: Shape, k_new, v_new, kbar) -> None:
+    """All rows of k_cache / v_cache bf16 [H, M+N, d] take k_new / v_new; kbar fp32 [H, n_b, d] (or None) gets the block means."""
+    for t, name in ((k_cache, "K_cache"), (v_cache, "V_cache"), (k_new, "K_new"), (v_new, "V_new")):
+        _need(t, torch.bfloat16, name)
+    if kbar is not None:
+        _need(kbar, torch.float32, "kbar")
+    if k_new.stride() != v_new.stride() or k_new.stride(2) != 1:
+        raise ValueError("K_new and V_new must share their strides, innermost 1")
+    _check(lib().focus_cache_refresh(_ptr(k_cache), _ptr(v_cache), C.byref(shape), _ptr(k_new), _ptr(v_new), k_new.stride(0),
+                                     k_new.stride(1), _ptr(kbar), _stream()))
 
 
 def sparse_layer(q, focus_idx, active_idx, counts, k, v, kbar, shape: Shape, n_keep: int, sink_idx, n_sink: int, scores,

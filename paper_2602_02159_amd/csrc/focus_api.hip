@@ -422,6 +422,22 @@ int focus_cache_update(void* K_cache, void* V_cache, const focus_shape* shape, c
   return FOCUS_OK;
 }
 
+int focus_cache_refresh(void* K_cache, void* V_cache, const focus_shape* shape, const void* K_new, const void* V_new,
+                        int64_t new_stride_h, int64_t new_stride_n, float* kbar, void* stream) {
+  if (int rc = check_shape(shape, false, true, true, false)) return rc;
+  if (!K_cache || !V_cache || !K_new || !V_new) return fail(FOCUS_EINVAL, "focus_cache_refresh: NULL pointer");
+  if (new_stride_n < shape->head_dim || (new_stride_n & 7) || new_stride_h < 0 || (new_stride_h & 7))
+    return fail(FOCUS_EINVAL, "focus_cache_refresh: strides of the new states invalid or not multiples of 8");
+  if (!aligned16(K_cache) || !aligned16(V_cache) || !aligned16(K_new) || !aligned16(V_new) || !aligned16(kbar))
+    return fail(FOCUS_EINVAL, "focus_cache_refresh: pointers must be 16-byte aligned");
+  if (K_cache == K_new || V_cache == V_new) return fail(FOCUS_EINVAL, "focus_cache_refresh: the new states must not alias the cache");
+  if (shape->n_heads > 65535) return fail(FOCUS_EUNSUPPORTED, "focus_cache_refresh: more than 65535 heads");
+  hipError_t e = launch_cache_refresh(K_cache, V_cache, *shape, K_new, V_new, new_stride_h, new_stride_n, kbar,
+                                      static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_cache_refresh", e);
+  return FOCUS_OK;
+}
+
 int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* counts, int32_t max_active, const void* K,
                       const void* V, const focus_shape* shape, int32_t n_sink, void* out, float* lse, float* col_mass,
                       int32_t* sink_idx, void* workspace, size_t ws_bytes, void* stream) {

@@ -68,6 +68,9 @@ hipError_t launch_token_confidence(const void* logits, int64_t row_stride, const
 hipError_t launch_cache_update(void* K_cache, void* V_cache, const focus_shape& s, const void* K_new, const void* V_new,
                                int64_t new_stride_h, int64_t new_stride_n, const int32_t* active_idx, const int32_t* counts,
                                int max_active, int row_base, hipStream_t st);
+// block entry: every cache row takes its new state; block means of the prompt keys from the same pass (kbar may be null)
+hipError_t launch_cache_refresh(void* K_cache, void* V_cache, const focus_shape& s, const void* K_new, const void* V_new,
+                                int64_t new_stride_h, int64_t new_stride_n, float* kbar, hipStream_t st);
 
 // ---- MFMA kernels (focus_mfma.hip)
 // mode 0: logits [H, L, q_pad] + part_ml out; mode 1: part_ml out only; mode 2: lse2 in, colpart [q_groups * H, L] out

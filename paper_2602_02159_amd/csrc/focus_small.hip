@@ -701,4 +701,86 @@ hipError_t launch_cache_update(void* K_cache, void* V_cache, const focus_shape& 
   return hipGetLastError();
 }
 
+// Block-entry cache refresh (Alg. 1: every position is recomputed when a block starts): all M + N rows of the K and V
+// caches take the new states, and the block means of the M prompt keys (Sec. 5.3) come out of the same pass, so the
+// new K is read once.  One workgroup per (chunk of B rows, head); chunks [0, n_b) are the prompt blocks, the rest
+// cover the response rows (copied only).  The mean is accumulated in exactly the order block_means_kernel uses
+// (thread (rr, c): rows rr, rr + RPP, ... of its 16-byte column slice; then the RPP partial rows in order), so the
+// two kernels give bit-identical K_bar.
+template <int D>
+__global__ __launch_bounds__(256) void cache_refresh_kernel(uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, int64_t ksh,
+                                                            int64_t ksn, int64_t vsh, int64_t vsn,
+                                                            const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
+                                                            int64_t nsh, int64_t nsn, int M, int L, int B, int n_b,
+                                                            float* __restrict__ kbar) {
+  constexpr int TPR = D / 8;
+  constexpr int RPP = 256 / TPR;
+  constexpr int UNROLL = 8;
+  __shared__ __attribute__((aligned(16))) float red[RPP][D];
+  const int b = blockIdx.x, h = blockIdx.y;
+  const bool prompt = b < n_b;
+  const int r0 = prompt ? b * B : M + (b - n_b) * B;
+  const int len = min(B, (prompt ? M : L) - r0);
+  const int c = threadIdx.x % TPR, rr = threadIdx.x / TPR;
+  const uint16_t* ksrc = Kn + (int64_t)h * nsh + (int64_t)r0 * nsn + c * 8;
+  const uint16_t* vsrc = Vn + (int64_t)h * nsh + (int64_t)r0 * nsn + c * 8;
+  uint16_t* kdst = Kc + (int64_t)h * ksh + (int64_t)r0 * ksn + c * 8;
+  uint16_t* vdst = Vc + (int64_t)h * vsh + (int64_t)r0 * vsn + c * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = rr; r < len; r += RPP * UNROLL) {
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int row = r + u * RPP;
+      v[u] = row < len ? load_stream16(ksrc + (int64_t)row * nsn) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int row = r + u * RPP;
+      add_bf16x8(acc, v[u]);
+      if (row < len) *reinterpret_cast<uint4*>(kdst + (int64_t)row * ksn) = v[u];
+    }
+  }
+  for (int r = rr; r < len; r += RPP * UNROLL) {
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int row = r + u * RPP;
+      if (row < len) v[u] = load_stream16(vsrc + (int64_t)row * nsn);
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int row = r + u * RPP;
+      if (row < len) *reinterpret_cast<uint4*>(vdst + (int64_t)row * vsn) = v[u];
+    }
+  }
+  if (!prompt || !kbar) return;  // uniform over the workgroup
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rr][c * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RPP; ++i) s += red[i][threadIdx.x];
+    kbar[((int64_t)h * n_b + b) * D + threadIdx.x] = s / (float)len;
+  }
+}
+
+hipError_t launch_cache_refresh(void* K_cache, void* V_cache, const focus_shape& s, const void* K_new, const void* V_new,
+                                int64_t new_stride_h, int64_t new_stride_n, float* kbar, hipStream_t st) {
+  const int n_b = ceil_div(s.n_ctx, s.block);
+  const dim3 grid(n_b + ceil_div(s.n_resp, s.block), s.n_heads);
+  uint16_t* kc = static_cast<uint16_t*>(K_cache);
+  uint16_t* vc = static_cast<uint16_t*>(V_cache);
+  const uint16_t* kn = static_cast<const uint16_t*>(K_new);
+  const uint16_t* vn = static_cast<const uint16_t*>(V_new);
+  if (s.head_dim == 128)
+    hipLaunchKernelGGL(cache_refresh_kernel<128>, grid, dim3(256), 0, st, kc, vc, s.k_stride_h, s.k_stride_n, s.v_stride_h,
+                       s.v_stride_n, kn, vn, new_stride_h, new_stride_n, s.n_ctx, s.n_ctx + s.n_resp, s.block, n_b, kbar);
+  else
+    hipLaunchKernelGGL(cache_refresh_kernel<64>, grid, dim3(256), 0, st, kc, vc, s.k_stride_h, s.k_stride_n, s.v_stride_h,
+                       s.v_stride_n, kn, vn, new_stride_h, new_stride_n, s.n_ctx, s.n_ctx + s.n_resp, s.block, n_b, kbar);
+  return hipGetLastError();
+}
+
 }  // namespace focus

@@ -548,6 +548,36 @@ def test_refresh_attn_strided_output_and_fewer_queries_than_keys(G):
     assert (buf[:, :, d:] == 7.0).all()
 
 
+@pytest.mark.parametrize("H,M,N,B,d", [(4, 1024, 64, 64, 128), (3, 1000, 37, 128, 64), (2, 70, 0, 32, 128), (2, 4100, 300, 128, 128)])
+def test_cache_refresh_copies_every_row_and_emits_block_means(G, H, M, N, B, d):
+    """Block entry: the caches equal the new states bit for bit (strided cache, padding untouched), K_bar equals the
+    oracle's block means and, bit for bit, focus_block_means of the new K."""
+    L = M + N
+    k_new, v_new = _rand_bf16(121, H, L, d).to(G.DEV), _rand_bf16(122, H, L, d).to(G.DEV)
+    kbuf = torch.full((H, L + 3, d + 8), 5.0, dtype=torch.bfloat16, device=G.DEV)
+    vbuf = torch.full((H, L + 3, d + 8), 6.0, dtype=torch.bfloat16, device=G.DEV)
+    k_cache, v_cache = kbuf[:, :L, :d], vbuf[:, :L, :d]
+    n_b = -(-M // B)
+    kbar = torch.full((H, n_b, d), float("nan"), dtype=torch.float32, device=G.DEV)
+    s = fb.make_shape(k_new[:, :1], k_cache, v_cache, M, B)
+    fb.cache_refresh(k_cache, v_cache, s, k_new, v_new, kbar)
+    torch.cuda.synchronize()
+    K_ref, V_ref = fo.cache_update(np.zeros((H, L, d)), np.zeros((H, L, d)), G.to_np(k_new), G.to_np(v_new), np.arange(L), 0)
+    assert np.array_equal(G.to_np(k_cache), K_ref) and np.array_equal(G.to_np(v_cache), V_ref)
+    assert (kbuf[:, L:] == 5.0).all() and (kbuf[:, :, d:] == 5.0).all() and (vbuf[:, L:] == 6.0).all() and (vbuf[:, :, d:] == 6.0).all()
+    ref = fo.block_means(G.to_np(k_new), M, B)
+    assert np.allclose(kbar.cpu().numpy(), ref, rtol=1e-5, atol=1e-5)
+    kbar2 = torch.empty_like(kbar)
+    fb.block_means(k_new, fb.make_shape(k_new[:, :1], k_new, v_new, M, B), kbar2)
+    torch.cuda.synchronize()
+    assert torch.equal(kbar, kbar2)
+    # copy only
+    kbuf.fill_(1.0)
+    fb.cache_refresh(k_cache, v_cache, s, k_new, v_new, None)
+    torch.cuda.synchronize()
+    assert torch.equal(k_cache, k_new)
+
+
 # ------------------------------------------------------------------------------------------------ around the step
 @pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
 def test_token_confidence(G, n_rows, vocab, pad):

@@ -100,6 +100,10 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     # refresh: NULL output, misaligned K
     assert L.focus_refresh_attn(fake, fake, fake, sp, None, None, None) == fb.FOCUS_EINVAL
     assert L.focus_refresh_attn(fake, C.c_void_p(4104), fake, sp, fake, None, None) == fb.FOCUS_EINVAL
+    # cache refresh: NULL source, source aliasing the cache, bad stride
+    assert L.focus_cache_refresh(fake, fake, sp, None, fake, 4096, 128, None, None) == fb.FOCUS_EINVAL
+    assert L.focus_cache_refresh(fake, fake, sp, fake, fake, 4096, 128, None, None) == fb.FOCUS_EINVAL
+    assert L.focus_cache_refresh(fake, fake, sp, C.c_void_p(8192), C.c_void_p(12288), 4096, 100, None, None) == fb.FOCUS_EINVAL
     # probe layer: NULL V, n_sink out of range, workspace too small
     assert L.focus_probe_layer(fake, fake, None, 8, fake, None, sp, 2, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
     assert L.focus_probe_layer(fake, fake, None, 8, fake, fake, sp, 5000, fake, None, None, fake, fake, big, None) == fb.FOCUS_EINVAL
