@@ -707,6 +707,7 @@ hipError_t launch_cache_update(void* K_cache, void* V_cache, const focus_shape& 
 // cover the response rows (copied only).  The mean is accumulated in exactly the order block_means_kernel uses
 // (thread (rr, c): rows rr, rr + RPP, ... of its 16-byte column slice; then the RPP partial rows in order), so the
 // two kernels give bit-identical K_bar.
+typedef unsigned uintx4_t __attribute__((ext_vector_type(4)));
 template <int D>
 __global__ __launch_bounds__(256) void cache_refresh_kernel(uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, int64_t ksh,
                                                             int64_t ksn, int64_t vsh, int64_t vsn,
@@ -738,7 +739,7 @@ __global__ __launch_bounds__(256) void cache_refresh_kernel(uint16_t* __restrict
     for (int u = 0; u < UNROLL; ++u) {
       const int row = r + u * RPP;
       add_bf16x8(acc, v[u]);
-      if (row < len) *reinterpret_cast<uint4*>(kdst + (int64_t)row * ksn) = v[u];
+      if (row < len) __builtin_nontemporal_store(__builtin_bit_cast(uintx4_t, v[u]), reinterpret_cast<uintx4_t*>(kdst + (int64_t)row * ksn));
     }
   }
   for (int r = rr; r < len; r += RPP * UNROLL) {
@@ -751,7 +752,7 @@ __global__ __launch_bounds__(256) void cache_refresh_kernel(uint16_t* __restrict
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int row = r + u * RPP;
-      if (row < len) *reinterpret_cast<uint4*>(vdst + (int64_t)row * vsn) = v[u];
+      if (row < len) __builtin_nontemporal_store(__builtin_bit_cast(uintx4_t, v[u]), reinterpret_cast<uintx4_t*>(vdst + (int64_t)row * vsn));
     }
   }
   if (!prompt || !kbar) return;  // uniform over the workgroup

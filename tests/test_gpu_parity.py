@@ -534,6 +534,24 @@ def test_refresh_attn_equals_full_bidirectional_attention(G, H, M, N, d):
     assert np.allclose(lse.cpu().numpy(), lse2.cpu().numpy(), atol=1e-3)
 
 
+def test_refresh_attn_full_size_sampled_rows(G):
+    """The launch bench.py --full-refresh times (32 heads, 32768 + 64 keys, d = 128, every position a query), checked on
+    sampled (head, row) pairs the oracle computes one by one."""
+    H, M, N, d = 32, 32768, 64, 128
+    L = M + N
+    q, k, v = (_rand_bf16(131 + i, H, L, d).to(G.DEV) for i in range(3))
+    out = torch.full((H, L, d), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    lse = torch.full((H, L), float("nan"), dtype=torch.float32, device=G.DEV)
+    fb.refresh_attn(q, k, v, fb.make_shape(q, k, v, M, 128, out), out, lse)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out.float()).any() and not torch.isnan(lse).any()
+    rows = np.array([0, 1, 31, 32, 127, 128, 16383, 16384, 32767, 32768, 32800, 32831])
+    for h in (0, 13, 31):
+        ref, ref_lse = fo.sparse_attention(G.to_np(q[h:h + 1]), rows, G.to_np(k[h:h + 1]), G.to_np(v[h:h + 1]), np.arange(M), M)
+        G.assert_attention_close(out[h:h + 1, rows], ref)
+        assert np.allclose(lse[h:h + 1, rows].cpu().numpy(), ref_lse, atol=2e-3)
+
+
 def test_refresh_attn_strided_output_and_fewer_queries_than_keys(G):
     H, M, N, d, n_q = 2, 700, 20, 128, 333
     q = _rand_bf16(111, n_q, H, d).to(G.DEV).permute(1, 0, 2)            # [L, H, d] storage
