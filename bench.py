@@ -212,6 +212,17 @@ def main() -> int:
                       "select"):
             st.issue(stage)
             sync()
+        # block entry: the cache rewrite, and the dense attention of every position at an eighth of the query rows
+        # (the counters are ratios; a launch over all rows would run twenty times longer under the profiler)
+        q0, k0, v0 = st.layers[0]
+        kc, vc = torch.empty_like(k0), torch.empty_like(v0)
+        kb = torch.empty(w.n_heads, w.n_blocks, w.head_dim, dtype=torch.float32, device=dev)
+        fb.cache_refresh(kc, vc, fb.make_shape(q0, kc, vc, w.n_ctx, w.block), k0, v0, kb)
+        sync()
+        q_part = torch.randn(w.n_heads, w.n_kv // 8, w.head_dim, device=dev).to(torch.bfloat16)
+        o_part = torch.empty_like(q_part)
+        fb.refresh_attn(q_part, k0, v0, fb.make_shape(q_part, k0, v0, w.n_ctx, w.block, o_part), o_part, None)
+        sync()
         print(json.dumps({"mode": "pmc", "copy_bytes": int(src.numel() * 4), "workload": w.name}))
         return 0
 

@@ -381,7 +381,7 @@ int focus_refresh_attn(const void* Q, const void* K, const void* V, const focus_
   if (!Q || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_refresh_attn: NULL pointer");
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out))
     return fail(FOCUS_EINVAL, "focus_refresh_attn: pointers must be 16-byte aligned");
-  if (ceil_div(shape->n_gen, 128) > 0x7fffffff / 2 || shape->n_heads > 65535)
+  if ((int64_t)ceil_div(shape->n_gen, 128) * shape->n_heads > 0x3fffffff)
     return fail(FOCUS_EUNSUPPORTED, "focus_refresh_attn: grid too large");
   if (shape->k_stride_n >= (1 << 25) || shape->v_stride_n >= (1 << 25))  // 32-row byte offsets are kept in 32 bits
     return fail(FOCUS_EUNSUPPORTED, "focus_refresh_attn: K/V row stride must be below 2^25 elements");

@@ -947,7 +947,7 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
 // v_dot2 over the packed bf16 pairs (two values per instruction, and the very values that enter the PV product),
 // the rescale of O runs only when some running maximum in the wavefront moved, and the ragged last sub-tile has a
 // loop body of its own.  No index lists, no key splits: each workgroup normalises and writes its own rows.
-// Grid (query blocks, heads), query blocks fastest: neighbouring workgroups share a head and find its K/V rows in L2.
+// One-dimensional grid over the (head, query block) list, dealt to the XCDs in contiguous eighths (see the kernel).
 // =====================================================================================================
 struct RefreshArgs {
   const uint16_t* Q;
@@ -957,6 +957,7 @@ struct RefreshArgs {
   float* lse;  // [H, n_q] natural log, or null
   int64_t qsh, qsn, ksh, ksn, vsh, vsn, osh, osn;
   int n_q, L;
+  int n_qb, n_work;  // query blocks per head; n_qb * heads
   float scale_log2;
 };
 
@@ -1011,8 +1012,15 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int qi = lane & 31, hh = lane >> 5;
-  const int h = blockIdx.y;
-  const int q_row = blockIdx.x * kRefreshQueries + wave * 32 + qi;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.  Launch slot i is
+  // therefore given work item (i % 8) * chunk + i / 8 of the (head, query block) list: an XCD walks one contiguous
+  // eighth of the list, so the workgroups resident on it at any time are neighbouring query blocks of ONE head and
+  // stream the same K/V rows through its L2 together.
+  const int chunk = (p.n_work + 7) >> 3;
+  const int work = (int)(blockIdx.x & 7u) * chunk + (int)(blockIdx.x >> 3);
+  if (work >= p.n_work) return;  // whole workgroup
+  const int h = work / p.n_qb;
+  const int q_row = (work - h * p.n_qb) * kRefreshQueries + wave * 32 + qi;
   const int n_tiles = (p.L + kSubTile - 1) / kSubTile;
   const int n_full = p.L / kSubTile;
 
@@ -1255,7 +1263,9 @@ hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, cons
   a.n_q = s.n_gen;
   a.L = s.n_ctx + s.n_resp;
   a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
-  const dim3 grid(ceil_div(s.n_gen, kRefreshQueries), s.n_heads);
+  a.n_qb = ceil_div(s.n_gen, kRefreshQueries);
+  a.n_work = a.n_qb * s.n_heads;
+  const dim3 grid(8 * ceil_div(a.n_work, 8));
   if (s.head_dim == 128)
     hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(256), 0, st, a);
   else
