@@ -356,13 +356,19 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   }
   // few sinks: the column-mass groups nominate, one small workgroup decides; many sinks: radix select over all of S
   const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
-  int32_t* cand = tournament ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  const bool prefilter = !tournament && sink_prefilter_fits(shape->n_ctx, n_sink, S);
+  int32_t* cand = (tournament || prefilter) ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  // with two nominees per group the index list fills at most a quarter of the buffer; their keys go into its second half
+  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand / 2;
   e = launch_column_mass(logits, two_pass, lse2, counts, max_active, two_pass ? p.q_groups * shape->n_heads : shape->n_heads,
-                         shape->n_heads, L, S, shape->n_ctx, n_sink, cand, st);
+                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, prefilter ? cand_keys : nullptr, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
   if (tournament) {
     e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N, tournament)", e);
+  } else if (prefilter) {
+    e = launch_sink_select(S, cand_keys, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N, bound and select)", e);
   } else if (n_sink > 0) {
     e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N)", e);
@@ -473,13 +479,19 @@ int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* c
     if (e != hipSuccess) return launch_fail("focus_probe_layer(column sums)", e);
   }
   const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
-  int32_t* cand = tournament ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  const bool prefilter = !tournament && sink_prefilter_fits(shape->n_ctx, n_sink, S);
+  int32_t* cand = (tournament || prefilter) ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
+  // with two nominees per group the index list fills at most a quarter of the buffer; their keys go into its second half
+  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand / 2;
   e = launch_column_mass(scratch, two_pass, lse2, counts, max_active, two_pass ? pa.q_groups * shape->n_heads : shape->n_heads,
-                         shape->n_heads, L, S, shape->n_ctx, n_sink, cand, st);
+                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, prefilter ? cand_keys : nullptr, st);
   if (e != hipSuccess) return launch_fail("focus_probe_layer(column mass)", e);
   if (tournament) {
     e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N, tournament)", e);
+  } else if (prefilter) {
+    e = launch_sink_select(S, cand_keys, shape->n_ctx, n_sink, sink_idx, st);
+    if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N, bound and select)", e);
   } else if (n_sink > 0) {
     e = launch_reduce_topk(nullptr, 0, nullptr, 0, S, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N)", e);

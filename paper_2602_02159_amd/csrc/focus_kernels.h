@@ -51,11 +51,19 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
 constexpr int kTournamentMaxSinks = 16;
 constexpr int kTournamentMaxCand = 4096;  // ceil(M / 128) * n_sink
 bool sink_tournament_fits(int M, int n_sink);
-// cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits).
+// cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits);
+// cand_keys: nullptr, or uint32 of the same size that receives their order keys + 1 (0 where cand holds -1).
 // pre_reduced = false: src = scaled logits [H, L, 16] of at most 16 queries, n_parts = H;
 // pre_reduced = true:  src = column sums [n_parts, L] from the second pass over K.
 hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
-                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st);
+                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, uint32_t* cand_keys,
+                              hipStream_t st);
+// Many sinks (N_sink > 16, n_ctx <= 32768, N_sink <= 1.4 per 128-key group): the groups nominate kPrefilterNominees each, the
+// N_sink-th largest nominee bounds the answer from below, and the exact selection runs over what clears the bound.
+constexpr int kPrefilterNominees = 2;
+bool sink_prefilter_fits(int M, int n_sink, const float* col_mass);
+hipError_t launch_sink_select(const float* col_mass, const uint32_t* cand_keys, int M, int n_sink, int32_t* sink_idx,
+                              hipStream_t st);
 hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st);
 

@@ -393,7 +393,7 @@ template <bool PRE>
 __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restrict__ src, const float* __restrict__ lse2,
                                                           const int32_t* __restrict__ counts, int max_active, int n_parts,
                                                           int H, int L, float* __restrict__ col_mass, int M, int n_sink,
-                                                          int32_t* __restrict__ cand) {
+                                                          int32_t* __restrict__ cand, uint32_t* __restrict__ cand_keys) {
   __shared__ float red[4][kMassKeys];
   __shared__ __attribute__((aligned(16))) uint32_t ckeys[256];
   __shared__ uint32_t ctotal;
@@ -456,7 +456,8 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
     if (threadIdx.x < 256) ckeys[threadIdx.x] = (pg == 0 && j < M) ? order_key(mass) + 1u : 0u;
     __syncthreads();
     if (threadIdx.x < kWave)
-      wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * kMassKeys);
+      wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * kMassKeys, nullptr,
+                   cand_keys ? cand_keys + (int64_t)blockIdx.x * n_sink : nullptr);
   }
 }
 
@@ -504,14 +505,152 @@ bool sink_tournament_fits(int M, int n_sink) {
 
 // pre_reduced = false: src = logits [H, L, 16], n_parts = H.  pre_reduced = true: src = column sums [n_parts, L].
 hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
-                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, hipStream_t st) {
-  if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
+                              int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, uint32_t* cand_keys,
+                              hipStream_t st) {
+  if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;  // n_sink: nominees per group
   if (pre_reduced)
     hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, src, lse2, counts,
-                       max_active, n_parts, H, L, col_mass, M, n_sink, cand);
+                       max_active, n_parts, H, L, col_mass, M, n_sink, cand, cand_keys);
   else
     hipLaunchKernelGGL(column_mass_kernel<false>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, src, lse2, counts,
-                       max_active, n_parts, H, L, col_mass, M, n_sink, cand);
+                       max_active, n_parts, H, L, col_mass, M, n_sink, cand, cand_keys);
+  return hipGetLastError();
+}
+
+// Top-N_sink beyond the tournament's limit (the paper's 1 % rule asks for hundreds of sinks), n = M <= 32768.
+// The column-mass kernel has nominated the two largest masses of every 128-key group.  The N_sink-th largest nominee
+// is a lower bound of the N_sink-th largest mass — that many positions are at least as large — so only positions
+// that reach it can be sinks: usually several hundred of the 32 768.  They are compacted in index order into LDS and
+// one wavefront selects the exact Top-N_sink among them (same total order, same tie rule, ascending output).  Only
+// if more than 1024 positions clear the bound (flat column masses) does the kernel fall back to the radix select
+// over all of them.  The bound only has to be valid, not tight: its search stops at bit kBoundLowBit and skips the bits
+// all nominees share.  Every thread keeps its run of 32 keys in registers; those loads and the load of the nominees'
+// keys (written by the column-mass kernel, one per thread) are in flight together.  col_mass must be 16-byte aligned.
+constexpr int kBoundLowBit = 10;
+__global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* __restrict__ col_mass,
+                                                                   const uint32_t* __restrict__ cand_keys, int n_cand, int M,
+                                                                   int n_sink, int32_t* __restrict__ sink_idx) {
+  __shared__ TopkShared sm;
+  __shared__ uint32_t cidx[kTopkThreads];
+  __shared__ uint32_t bound_sh;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int chunk = (((M + kTopkThreads - 1) / kTopkThreads) + 3) & ~3;  // <= kTopkRegKeys (launcher)
+  const int c0 = min(tid * chunk, M), c1 = min(c0 + chunk, M);
+  TOPK_STAMP(0);
+  const uint32_t nominee = tid < n_cand ? cand_keys[tid] : 0u;  // key + 1 of a nominee, 0 = none; n_cand <= 512
+  float4 v[kTopkRegKeys / 4];
+#pragma unroll
+  for (int r4 = 0; r4 < kTopkRegKeys / 4; ++r4) {
+    const int i = c0 + 4 * r4;
+    v[r4] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i + 3 < c1) {
+      v[r4] = *reinterpret_cast<const float4*>(col_mass + i);
+    } else {
+      if (i < c1) v[r4].x = col_mass[i];
+      if (i + 1 < c1) v[r4].y = col_mass[i + 1];
+      if (i + 2 < c1) v[r4].z = col_mass[i + 2];
+    }
+  }
+  sm.keys[tid] = nominee;
+  uint32_t rk[kTopkRegKeys];  // key + 1, 0 = no such position
+#pragma unroll
+  for (int r4 = 0; r4 < kTopkRegKeys / 4; ++r4) {
+    const int i = c0 + 4 * r4;
+    rk[4 * r4] = i < c1 ? order_key(v[r4].x) + 1u : 0u;
+    rk[4 * r4 + 1] = i + 1 < c1 ? order_key(v[r4].y) + 1u : 0u;
+    rk[4 * r4 + 2] = i + 2 < c1 ? order_key(v[r4].z) + 1u : 0u;
+    rk[4 * r4 + 3] = i + 3 < c1 ? order_key(v[r4].w) + 1u : 0u;
+  }
+  __syncthreads();
+  TOPK_STAMP(1);
+  if (tid < kWave) {  // a lower bound of the N_sink-th largest nominee key: bitwise search over ballot counts, 8 nominees per lane
+    uint32_t kv[8];
+    const uint4 k0 = reinterpret_cast<const uint4*>(sm.keys)[lane * 2], k1 = reinterpret_cast<const uint4*>(sm.keys)[lane * 2 + 1];
+    kv[0] = k0.x; kv[1] = k0.y; kv[2] = k0.z; kv[3] = k0.w;
+    kv[4] = k1.x; kv[5] = k1.y; kv[6] = k1.z; kv[7] = k1.w;
+    uint32_t nvalid = 0, a = 0xffffffffu, o = 0u;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      nvalid += (uint32_t)__popcll(__ballot(kv[r] != 0u));
+      a &= kv[r] != 0u ? kv[r] : 0xffffffffu;
+      o |= kv[r];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      a &= __shfl_xor(a, off, kWave);
+      o |= __shfl_xor(o, off, kWave);
+    }
+    uint32_t T = 1u;  // fewer nominees than sinks asked for: every position is a candidate
+    if (nvalid >= (uint32_t)n_sink) {
+      const uint32_t same = ~(a ^ o);
+      T = 0u;
+      for (int bit = 31; bit >= kBoundLowBit; --bit) {
+        if ((same >> bit) & 1u) {
+          T |= a & (1u << bit);
+          continue;
+        }
+        const uint32_t c = T | (1u << bit);
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cnt += (uint32_t)__popcll(__ballot(kv[r] >= c));
+        if (cnt >= (uint32_t)n_sink) T = c;
+      }
+    }
+    if (lane == 0) bound_sh = max(T, 1u);
+    TOPK_STAMP(2);
+  }
+  __syncthreads();
+  const uint32_t bound = bound_sh;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int r = 0; r < kTopkRegKeys; ++r) mine += rk[r] >= bound;
+  uint32_t n_clear;
+  uint32_t pos = block_exclusive_scan(mine, sm.wsum, &n_clear);
+  TOPK_STAMP(3);
+  if (n_clear <= (uint32_t)kTopkThreads) {  // uniform
+    if (tid >= (int)n_clear) sm.keys[tid] = 0u;  // the nominee keys are no longer needed (everyone passed the scan's barriers)
+#pragma unroll
+    for (int r = 0; r < kTopkRegKeys; ++r) {
+      if (rk[r] >= bound) {
+        sm.keys[pos] = rk[r];
+        cidx[pos] = (uint32_t)(c0 + r);
+        ++pos;
+      }
+    }
+    __syncthreads();
+    TOPK_STAMP(4);
+    if (tid < kWave) {
+      if (n_clear <= 256u)
+        wave_topk<4, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
+      else if (n_clear <= 512u)
+        wave_topk<8, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
+      else
+        wave_topk<16, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
+      TOPK_STAMP(5);
+    }
+    return;
+  }
+  auto keyfn = [=](int i, uint32_t& key) -> bool {
+    key = order_key(col_mass[i]);
+    return true;
+  };
+  block_topk(keyfn, M, n_sink, sink_idx, nullptr, nullptr, sm, col_mass);
+}
+
+// the bound-then-select path: more sinks than the tournament takes, a run of at most 32 keys per thread, and at most
+// 1.4 sinks per 128-key group (the paper's 1 % rule asks for 1.28): with two nominees per group the bound is then the
+// 0.7 quantile of the nominees or higher — closer to their minimum it lets too many positions through and the kernel
+// would pay for the bound and for the radix select
+bool sink_prefilter_fits(int M, int n_sink, const float* col_mass) {
+  return n_sink > kTournamentMaxSinks && M <= kTopkThreads * kTopkRegKeys && 10 * n_sink <= 14 * (M / kMassKeys) &&
+         (reinterpret_cast<uintptr_t>(col_mass) & 15u) == 0;
+}
+
+hipError_t launch_sink_select(const float* col_mass, const uint32_t* cand_keys, int M, int n_sink, int32_t* sink_idx,
+                              hipStream_t st) {
+  if (!sink_prefilter_fits(M, n_sink, col_mass)) return hipErrorInvalidValue;
+  const int n_cand = ceil_div(M, kMassKeys) * kPrefilterNominees;  // <= 512
+  hipLaunchKernelGGL(sink_select_kernel, dim3(1), dim3(kTopkThreads), 0, st, col_mass, cand_keys, n_cand, M, n_sink, sink_idx);
   return hipGetLastError();
 }
 

@@ -75,11 +75,14 @@ struct TopkShared {
 // lane l holds keys[l * KPL .. l * KPL + KPL).  A bitwise search finds T, the k-th largest key (32 steps of KPL
 // compares and ballot popcounts); everything above T is selected, and of the keys equal to T the ones with the
 // lowest indices until k are reached.  Output positions come from ballot prefix counts, so `out` is ascending.
-// Writes out[0..k) = base + index (tail -1), flags[0..n) if not null, and *total.  Must be called by all 64 lanes of one
-// wavefront.
-template <int KPL>
+// Writes out[0..k) = base + index, or remap[index] when remap is given (tail -1), flags[0..n) if not null, and *total.
+// Must be called by all 64 lanes of one wavefront.
+// SKIP_COMMON: bits in which all candidate keys agree are taken over without a search step (worth its two wavefront
+// reductions when the keys are close together, as the column masses that clear a lower bound are).
+// out_keys, if given, receives the selected keys (key + 1) in the same positions.
+template <int KPL, bool SKIP_COMMON = false>
 __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, int32_t* out, uint8_t* flags, uint32_t* total,
-                                          int base = 0) {
+                                          int base = 0, const uint32_t* remap = nullptr, uint32_t* out_keys = nullptr) {
   const int lane = threadIdx.x & 63;
   uint32_t kv[KPL];
 #pragma unroll
@@ -93,7 +96,27 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
   const uint32_t k_eff = min((uint32_t)max(k, 0), nvalid);
   uint32_t T = 0;
   if (k_eff > 0) {
+    uint32_t common = 0, same = 0;  // same: bits on which every candidate agrees; common: their value
+    if (SKIP_COMMON) {
+      uint32_t a = 0xffffffffu, o = 0u;
+#pragma unroll
+      for (int r = 0; r < KPL; ++r) {
+        a &= kv[r] != 0u ? kv[r] : 0xffffffffu;
+        o |= kv[r];
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        a &= __shfl_xor(a, off, kWave);
+        o |= __shfl_xor(o, off, kWave);
+      }
+      common = a;
+      same = ~(a ^ o);
+    }
     for (int bit = 31; bit >= 0; --bit) {
+      if (SKIP_COMMON && ((same >> bit) & 1u)) {  // wave-uniform
+        T |= common & (1u << bit);
+        continue;
+      }
       const uint32_t cand = T | (1u << bit);
       uint32_t cnt = 0;
 #pragma unroll
@@ -125,10 +148,16 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
     const int idx = lane * KPL + r;
-    if (sel[r]) out[pos++] = base + idx;
+    if (sel[r]) {
+      if (out_keys) out_keys[pos] = kv[r];
+      out[pos++] = remap ? (int32_t)remap[idx] : base + idx;
+    }
     if (flags && idx < n) flags[idx] = (uint8_t)sel[r];
   }
-  for (int i = (int)k_eff + lane; i < k; i += kWave) out[i] = -1;
+  for (int i = (int)k_eff + lane; i < k; i += kWave) {
+    out[i] = -1;
+    if (out_keys) out_keys[i] = 0u;
+  }
   if (lane == 0) *total = k_eff;
 }
 
