@@ -440,11 +440,15 @@ def main() -> int:
             pmc = json.load(fh)
         # the counters are taken on the stand-alone stages; the attention kernel appears there without the fused Top-C
         # prologue (<128, 1, 0>), a name the dense comparison shares: its smallest dispatch is the sparse one
-        want = f"sparse_attn_kernel<{d}, {qtw}, 0>" if dom_kernel == "sparse_attn" else kernel_name.split(" and ")[0]
+        want = [f"sparse_attn_kernel<{d}, {qtw}, 0>" if dom_kernel == "sparse_attn" else kernel_name.split(" and ")[0]]
+        if dom_kernel == "find_sinks":   # every kernel of the chain: logits (one or two passes over K), row statistics, column mass, Top-N
+            want += ["lse_combine_kernel", "column_mass_kernel", "sink_final_kernel", "sink_select_kernel", "reduce_topk_kernel<0>"]
+            if qtw > 1:
+                want.append(f"qk_logits_kernel<{d}, {qtw}, 2>")
         which = "min" if dom_kernel == "sparse_attn" else "max"
         for name, v in pmc["kernels"].items():
-            if want in name:
-                traffic = int(v[f"fetch_bytes_{which}"] + v[f"write_bytes_{which}"])
+            if any(x in name for x in want):
+                traffic = (traffic or 0) + int(v[f"fetch_bytes_{which}"] + v[f"write_bytes_{which}"])
     except (OSError, KeyError, ValueError):
         pass
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": ds["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
