@@ -516,7 +516,8 @@ def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
 
 
 # ------------------------------------------------------------------------------------------------ block-entry refresh
-@pytest.mark.parametrize("H,M,N,d", [(4, 1024, 32, 64), (2, 2050, 33, 128), (3, 100, 7, 128), (1, 5, 0, 64), (2, 4096, 64, 128)])
+@pytest.mark.parametrize("H,M,N,d", [(4, 1024, 32, 64), (2, 2050, 33, 128), (3, 100, 7, 128), (1, 5, 0, 64), (2, 4096, 64, 128),
+                                     (2, 40, 9, 128), (2, 64, 32, 64), (33, 300, 20, 128)])   # two and three key sub-tiles; a head count that is no multiple of 8
 def test_refresh_attn_equals_full_bidirectional_attention(G, H, M, N, d):
     """Every position attends to every position: against the oracle's dense reduction, an independent fp64
     scaled_dot_product_attention, and focus_sparse_attn with everything kept."""
