@@ -95,7 +95,12 @@ PAPER32K = Workload(name="paper32k", n_layers=1, n_heads=32, head_dim=128, n_ctx
                     k_focus=4, window=8, n_keep=256, n_sink=327, sink_positions=_seeded_sinks(_BASE_SEED + 5, 32768, 4),
                     conf_model="correlated", seed=_BASE_SEED + 5)
 
-WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K, PAPER32K)}
+# The same with the paper's generation layout: 256 response tokens decoded in blocks of 32.  The queries are the 32
+# positions of the current block; all 256 response rows are keys that are always kept.
+PAPER32K_GEN256 = PAPER32K.with_(name="paper32k_gen256", n_resp=256, n_gen=32, seed=_BASE_SEED + 6,
+                                 sink_positions=_seeded_sinks(_BASE_SEED + 6, 32768, 4))
+
+WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K, PAPER32K, PAPER32K_GEN256)}
 
 
 def strong_sinks(w: Workload, logit_shift: float = 6.0) -> Workload:
