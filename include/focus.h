@@ -7,6 +7,7 @@
  * Alg. 1 runs them:
  *
  *     focus_select_queries   once per denoising step            -> I_focus, I_active
+ *     focus_expand_groups    (grouped-query attention only) the same lists for the rows of all query heads of a group
  *     focus_find_sinks       once per step, at the probe layer  -> I_sink   (reused unchanged by all deeper layers)
  *     focus_block_means      whenever the prompt K of a layer is refreshed -> K_bar (cacheable)
  *     focus_block_scores     per sparse layer                   -> R_b, B_relevant
@@ -95,6 +96,22 @@ typedef enum focus_fn {
 int focus_select_queries(const float* conf, const uint8_t* masked, int32_t n_gen, int32_t k, int32_t window,
                          int32_t lo, int32_t hi, int32_t* focus_idx, int32_t* active_idx, int32_t max_active,
                          int32_t* counts, void* stream);
+
+/*
+ * Grouped-query attention (several query heads share one K/V head).  Every entry point takes ONE head count; a model
+ * with H_q query heads and H_kv = H_q / group K/V heads is run as H_kv heads whose query rows are the rows of all
+ * `group` query heads of the group: with Q stored head-major, [H_q, n_gen, d] (q_stride_h = n_gen * q_stride_n), the
+ * same memory is the tensor [H_kv, group * n_gen, d] — pass n_heads = H_kv, n_gen = group * n_gen, q_stride_h and
+ * o_stride_h multiplied by `group` — and position i of the g-th head of a group is row g * n_gen + i.  Eq. 6, Eq. 7
+ * and Eq. 9 are unchanged by this view (their means run over the same (head, query) pairs), and K and V are read once
+ * per K/V head.  This call turns the index lists of focus_select_queries into the lists of that view.
+ *   focus_idx  [dev] int32[max_focus], active_idx [dev] int32[max_active], counts [dev] int32[2] or NULL (= lists are full)
+ *   focus_out  [dev] int32[group * max_focus], active_out [dev] int32[group * max_active]: entry a of head g at
+ *              g * n + a (n = number of valid entries), ascending when the input is, tail -1;  counts_out [dev] int32[2]
+ */
+int focus_expand_groups(const int32_t* focus_idx, int32_t max_focus, const int32_t* active_idx, int32_t max_active,
+                        const int32_t* counts, int32_t n_gen, int32_t group, int32_t* focus_out, int32_t* active_out,
+                        int32_t* counts_out, void* stream);
 
 /*
  * Representative key of every prompt block (Sec. 5.3, "Block-wise token pruning"):

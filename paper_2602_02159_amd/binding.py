@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libfocus_hip.so")
 FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0, -1, -2, -3, -4
 FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER = 1, 2, 3, 4, 5
 
-EXPORTS = ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
+EXPORTS = ("focus_select_queries", "focus_expand_groups", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
            "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn", "focus_cache_refresh",
            "focus_token_confidence", "focus_token_confidence_workspace", "focus_cache_update",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
@@ -52,6 +52,7 @@ def lib() -> C.CDLL:
         p, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         sp = C.POINTER(Shape)
         L.focus_select_queries.argtypes = [p, p, i32, i32, i32, i32, i32, p, p, i32, p, p]
+        L.focus_expand_groups.argtypes = [p, i32, p, i32, p, i32, i32, p, p, p, p]
         L.focus_block_means.argtypes = [p, sp, p, p]
         L.focus_block_scores.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, sz, p]
         L.focus_find_sinks.argtypes = [p, p, p, i32, p, sp, i32, p, p, p, sz, p]
@@ -66,7 +67,7 @@ def lib() -> C.CDLL:
         L.focus_cache_update.argtypes = [p, p, sp, p, p, C.c_int64, C.c_int64, p, p, i32, i32, p]
         L.focus_block_partials.argtypes = [p, p, p, i32, p, p, sp, p, p]
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
-        for name in ("focus_select_queries", "focus_block_means", "focus_block_scores", "focus_find_sinks",
+        for name in ("focus_select_queries", "focus_expand_groups", "focus_block_means", "focus_block_scores", "focus_find_sinks",
                      "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
                      "focus_probe_layer", "focus_refresh_attn", "focus_token_confidence", "focus_cache_update", "focus_cache_refresh"):
             getattr(L, name).restype = C.c_int
@@ -144,6 +145,12 @@ def select_queries(conf, masked, k: int, window: int, lo: int, hi: int, focus_id
     _need(conf, torch.float32, "conf")
     _check(lib().focus_select_queries(_ptr(conf), _ptr(masked), conf.numel(), k, window, lo, hi, _ptr(focus_idx),
                                       _ptr(active_idx), active_idx.numel(), _ptr(counts), _stream()))
+
+
+def expand_groups(focus_idx, active_idx, counts, n_gen: int, group: int, focus_out, active_out, counts_out) -> None:
+    """Index lists of select_queries -> lists of rows g * n_gen + i of the [H_kv, group * n_gen, d] view of Q."""
+    _check(lib().focus_expand_groups(_ptr(focus_idx), focus_idx.numel(), _ptr(active_idx), active_idx.numel(), _ptr(counts),
+                                     n_gen, group, _ptr(focus_out), _ptr(active_out), _ptr(counts_out), _stream()))
 
 
 def block_means(k, shape: Shape, kbar) -> None:

@@ -256,6 +256,22 @@ int focus_select_queries(const float* conf, const uint8_t* masked, int32_t n_gen
   return FOCUS_OK;
 }
 
+int focus_expand_groups(const int32_t* focus_idx, int32_t max_focus, const int32_t* active_idx, int32_t max_active,
+                        const int32_t* counts, int32_t n_gen, int32_t group, int32_t* focus_out, int32_t* active_out,
+                        int32_t* counts_out, void* stream) {
+  if (!focus_idx || !active_idx || !focus_out || !active_out || !counts_out)
+    return fail(FOCUS_EINVAL, "focus_expand_groups: NULL pointer");
+  if (n_gen < 1 || group < 1 || max_focus < 1 || max_active < 1)
+    return fail(FOCUS_EINVAL, "focus_expand_groups: n_gen=%d group=%d max_focus=%d max_active=%d must be positive", n_gen, group,
+                max_focus, max_active);
+  if ((int64_t)group * n_gen > (1 << 30) || (int64_t)group * std::max(max_focus, max_active) > (1 << 30))
+    return fail(FOCUS_EUNSUPPORTED, "focus_expand_groups: more than 2^30 rows");
+  hipError_t e = launch_expand_groups(focus_idx, max_focus, active_idx, max_active, counts, n_gen, group, focus_out, active_out,
+                                      counts_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return launch_fail("focus_expand_groups", e);
+  return FOCUS_OK;
+}
+
 int focus_block_means(const void* K, const focus_shape* shape, float* kbar, void* stream) {
   if (int rc = check_shape(shape, false, true, false, false)) return rc;
   if (!K || !kbar) return fail(FOCUS_EINVAL, "focus_block_means: NULL pointer");

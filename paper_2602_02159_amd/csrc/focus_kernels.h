@@ -34,6 +34,10 @@ SplitPlan plan_logits(const focus_shape& s, int max_active);
 hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n_gen, int k, int window, int lo,
                                  int hi, int32_t* focus_idx, int32_t* active_idx, int max_active, int32_t* counts,
                                  hipStream_t st);
+// grouped-query attention: index lists of the selection -> lists of rows g * n_gen + i of the [H_kv, group * n_gen, d] view of Q
+hipError_t launch_expand_groups(const int32_t* focus_idx, int max_focus, const int32_t* active_idx, int max_active,
+                                const int32_t* counts, int n_gen, int group, int32_t* focus_out, int32_t* active_out,
+                                int32_t* counts_out, hipStream_t st);
 hipError_t launch_block_means(const void* K, const focus_shape& s, float* kbar, hipStream_t st);
 // one scan of K that yields the per-head partial relevances (and, if kbar is not null, the block means)
 hipError_t launch_block_means_relevance(const void* K, const void* Q, const int32_t* focus_idx, const int32_t* counts,

@@ -70,6 +70,49 @@ hipError_t launch_select_queries(const float* conf, const uint8_t* masked, int n
   return hipGetLastError();
 }
 
+// Grouped-query attention: the `group` query heads that share a K/V head are presented to every other kernel as
+// `group` times as many query rows of that head (row g * n_gen + i for position i of the g-th head of the group).
+// This turns the index lists of the selection into lists of such rows: list entry a of head g lands at g * n + a,
+// n the number of valid entries, so the output is ascending when the input is; the tail is filled with -1.
+__global__ __launch_bounds__(256) void expand_groups_kernel(const int32_t* __restrict__ focus_idx, int max_focus,
+                                                            const int32_t* __restrict__ active_idx, int max_active,
+                                                            const int32_t* __restrict__ counts, int n_gen, int group,
+                                                            int32_t* __restrict__ focus_out, int32_t* __restrict__ active_out,
+                                                            int32_t* __restrict__ counts_out) {
+  const int n_f = counts ? min(max(counts[0], 0), max_focus) : max_focus;
+  const int n_a = counts ? min(max(counts[1], 0), max_active) : max_active;
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < group * max_focus) {
+    int v = -1;
+    if (t < group * n_f) {
+      const int i = focus_idx[t % n_f];
+      if (i >= 0 && i < n_gen) v = (t / n_f) * n_gen + i;
+    }
+    focus_out[t] = v;
+  }
+  if (t < group * max_active) {
+    int v = -1;
+    if (t < group * n_a) {
+      const int i = active_idx[t % n_a];
+      if (i >= 0 && i < n_gen) v = (t / n_a) * n_gen + i;
+    }
+    active_out[t] = v;
+  }
+  if (t == 0) {
+    counts_out[0] = group * n_f;
+    counts_out[1] = group * n_a;
+  }
+}
+
+hipError_t launch_expand_groups(const int32_t* focus_idx, int max_focus, const int32_t* active_idx, int max_active,
+                                const int32_t* counts, int n_gen, int group, int32_t* focus_out, int32_t* active_out,
+                                int32_t* counts_out, hipStream_t st) {
+  const int n = group * std::max(max_focus, max_active);
+  hipLaunchKernelGGL(expand_groups_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, focus_idx, max_focus, active_idx,
+                     max_active, counts, n_gen, group, focus_out, active_out, counts_out);
+  return hipGetLastError();
+}
+
 // =====================================================================================================
 // Top-k over a float array that may first have to be assembled from per-head partial sums:
 //   values[j] = scale * sum_{h < n_parts} part[h * n + j]   (fixed order over h), written to values_out,

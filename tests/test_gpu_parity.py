@@ -515,6 +515,54 @@ def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
         assert all(torch.equal(a, b["out"]) for a, b in zip(eager, st.bufs))
 
 
+# ------------------------------------------------------------------------------------------------ grouped-query attention
+@pytest.mark.parametrize("H_kv,group,M,N,d,B,n_gen,k,window,n_keep,n_sink", [
+    (2, 4, 2048, 32, 128, 64, 32, 6, 0, 5, 3),       # 24 query rows per K/V head: two query tiles
+    (4, 7, 4096, 64, 128, 128, 64, 4, 8, 8, 20),     # 28 heads on 4 K/V heads, window-expanded queries: several query groups
+    (3, 2, 1000, 37, 64, 48, 40, 16, 0, 4, 2),       # ragged sizes, d = 64
+])
+def test_grouped_query_attention_through_the_row_view(G, H_kv, group, M, N, d, B, n_gen, k, window, n_keep, n_sink):
+    """Several query heads per K/V head: the device runs H_kv heads over the [H_kv, group * n_gen, d] view of Q with the
+    expanded index lists and reads every K/V head once; the oracle runs all H_q heads separately against K/V repeated
+    per query head.  Sinks, kept blocks and attention must agree."""
+    H_q, L = H_kv * group, M + N
+    q = _rand_bf16(141, H_q, n_gen, d).to(G.DEV)                      # head-major: [H_q, n_gen, d]
+    k_, v_ = _rand_bf16(142, H_kv, L, d).to(G.DEV), _rand_bf16(143, H_kv, L, d).to(G.DEV)
+    conf = np.random.default_rng(144).random(n_gen).astype(np.float32)
+    # oracle: plain multi-head attention over repeated K/V
+    Q, K, V = G.to_np(q), np.repeat(G.to_np(k_), group, axis=0), np.repeat(G.to_np(v_), group, axis=0)
+    focus_ref = fo.select_focus(conf, None, k)
+    active_ref = fo.expand_window(focus_ref, window, 0, n_gen)
+    S_ref = fo.sink_scores(Q, active_ref, K)
+    sinks_ref = fo.select_sinks(S_ref, M, n_sink)
+    lay = fo.focus_layer(Q, K, V, focus_ref, active_ref, sinks_ref, M, B, n_keep)
+    assert fo.decision_margin(S_ref, n_sink, np.arange(L) < M) > 1e-5 and fo.decision_margin(lay["R"], n_keep) > 1e-5
+    # device
+    focus, active, counts = G.gpu_select(conf, None, k, window, 0, n_gen)
+    f2 = torch.full((group * focus.numel(),), -7, dtype=torch.int32, device=G.DEV)
+    a2 = torch.full((group * active.numel(),), -7, dtype=torch.int32, device=G.DEV)
+    c2 = torch.zeros(2, dtype=torch.int32, device=G.DEV)
+    fb.expand_groups(focus, active, counts, n_gen, group, f2, a2, c2)
+    torch.cuda.synchronize()
+    n_f, n_a = len(focus_ref), len(active_ref)
+    assert c2.cpu().tolist() == [group * n_f, group * n_a]
+    want_a = [g * n_gen + i for g in range(group) for i in active_ref.tolist()]
+    assert a2.cpu().tolist() == want_a + [-1] * (a2.numel() - len(want_a))
+    want_f = [g * n_gen + i for g in range(group) for i in focus_ref.tolist()]
+    assert f2.cpu().tolist() == want_f + [-1] * (f2.numel() - len(want_f))
+    qv = q.view(H_kv, group * n_gen, d)                               # the same memory, one row list per K/V head
+    col, sinks = G.gpu_find_sinks(qv, a2, c2, k_, M, B, n_sink)
+    scores, kept = G.gpu_block_scores(qv, f2, c2, k_, None, M, B, n_keep)
+    out, lse = G.gpu_sparse_attn(qv, a2, c2, k_, v_, M, B, kept, sinks)
+    assert np.allclose(col.cpu().numpy(), S_ref, rtol=2e-4, atol=1e-10)
+    assert sinks.cpu().tolist() == sinks_ref.tolist()
+    assert np.allclose(scores.cpu().numpy(), lay["R"], atol=2e-6)
+    assert kept.cpu().tolist() == lay["blocks"].tolist()
+    # output slot g * n_a + a of K/V head kv is active query a of query head kv * group + g
+    got = out[:, :group * n_a].reshape(H_kv, group, n_a, d).reshape(H_q, n_a, d)
+    G.assert_attention_close(got, lay["out"])
+
+
 # ------------------------------------------------------------------------------------------------ block-entry refresh
 @pytest.mark.parametrize("H,M,N,d", [(4, 1024, 32, 64), (2, 2050, 33, 128), (3, 100, 7, 128), (1, 5, 0, 64), (2, 4096, 64, 128),
                                      (2, 40, 9, 128), (2, 64, 32, 64), (33, 300, 20, 128)])   # two and three key sub-tiles; a head count that is no multiple of 8

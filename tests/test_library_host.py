@@ -100,6 +100,9 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     # refresh: NULL output, misaligned K
     assert L.focus_refresh_attn(fake, fake, fake, sp, None, None, None) == fb.FOCUS_EINVAL
     assert L.focus_refresh_attn(fake, C.c_void_p(4104), fake, sp, fake, None, None) == fb.FOCUS_EINVAL
+    # group expansion: NULL list, non-positive group
+    assert L.focus_expand_groups(None, 4, fake, 4, None, 32, 2, fake, fake, fake, None) == fb.FOCUS_EINVAL
+    assert L.focus_expand_groups(fake, 4, fake, 4, None, 32, 0, fake, fake, fake, None) == fb.FOCUS_EINVAL
     # cache refresh: NULL source, source aliasing the cache, bad stride
     assert L.focus_cache_refresh(fake, fake, sp, None, fake, 4096, 128, None, None) == fb.FOCUS_EINVAL
     assert L.focus_cache_refresh(fake, fake, sp, fake, fake, 4096, 128, None, None) == fb.FOCUS_EINVAL
