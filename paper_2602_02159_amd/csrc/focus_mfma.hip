@@ -971,7 +971,8 @@ template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
-constexpr int kRefreshQueries = 128;  // queries per workgroup of the refresh kernel
+constexpr int kRefreshWaves = 8;                        // wavefronts per workgroup of the refresh kernel, 32 queries each
+constexpr int kRefreshQueries = 32 * kRefreshWaves;  // queries per workgroup
 
 // A operand of O^T += V^T P^T (32x32x16) for d tile `dt` and k-step `ks`: lane (dcol = lane % 32, hh) needs
 // V[16 ks + 8 (e / 4) + 4 hh + e % 4][32 dt + dcol], e = 0..7 — two transposed reads of four consecutive rows each.
@@ -1001,12 +1002,14 @@ __device__ __forceinline__ bf16x8 read_v_operand32(const char* stageV, int dt, i
 }
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs p) {
+__global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(const RefreshArgs p) {
   using G = Geo<D>;
   constexpr int kKS = D / 16;                    // k-steps of K Q^T
   constexpr int kDT = D / 32;                    // 32-wide d tiles of V^T P^T
   constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage of one sub-tile
-  constexpr int NL = G::kLoads / 2;              // loads per wavefront and sub-tile: half of the K or of the V rows
+  constexpr int kShare = kRefreshWaves / 2;      // wavefronts that share the K (or the V) rows of a sub-tile
+  constexpr int NL = G::kLoads / kShare;         // loads per wavefront and sub-tile
+  static_assert(G::kLoads % kShare == 0 && NL >= 1, "every wavefront stages at least one load");
   __shared__ __attribute__((aligned(16))) char stage[2][kBufBytes];
 
   const int lane = threadIdx.x & 63;
@@ -1026,8 +1029,8 @@ __global__ __launch_bounds__(256, 2) void refresh_attn_kernel(const RefreshArgs 
 
   // this wavefront's share of every sub-tile: wavefronts 0, 1 the two halves of the K rows, 2, 3 of the V rows.
   // Row addresses: a scalar base that moves by 32 rows per sub-tile plus per-lane byte offsets fixed for the launch.
-  const bool is_v = wave >= 2;
-  const int first = (wave & 1) * NL;
+  const bool is_v = wave >= kShare;
+  const int first = (wave % kShare) * NL;
   const char* src = reinterpret_cast<const char*>(is_v ? p.V + (int64_t)h * p.vsh : p.K + (int64_t)h * p.ksh);
   const int64_t row_bytes = (is_v ? p.vsn : p.ksn) * 2;
   const int64_t tile_bytes = row_bytes * kSubTile;
@@ -1267,9 +1270,9 @@ hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, cons
   a.n_work = a.n_qb * s.n_heads;
   const dim3 grid(8 * ceil_div(a.n_work, 8));
   if (s.head_dim == 128)
-    hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(64 * kRefreshWaves), 0, st, a);
   else
-    hipLaunchKernelGGL(refresh_attn_kernel<64>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(refresh_attn_kernel<64>, grid, dim3(64 * kRefreshWaves), 0, st, a);
   return hipGetLastError();
 }
 
