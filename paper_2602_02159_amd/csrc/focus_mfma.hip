@@ -935,8 +935,8 @@ hipError_t launch_sparse_attn(const void* Q, const int32_t* active_idx, const in
 // =====================================================================================================
 // Block-entry refresh (Alg. 1, I_active = all positions): dense bidirectional attention of EVERY row of Q over every
 // key — the one MFMA-bound launch of the method (4 n_q L d flops per head against 2 L d 2 bytes of K and V).
-// A workgroup holds 128 consecutive queries, 32 per wavefront, and walks the key axis in 32-row sub-tiles shared by
-// its four wavefronts and double-buffered through registers: while sub-tile t is multiplied, sub-tile t + 1 sits in
+// A workgroup holds 256 consecutive queries, 32 per wavefront, and walks the key axis in 32-row sub-tiles shared by
+// its eight wavefronts and double-buffered through registers: while sub-tile t is multiplied, sub-tile t + 1 sits in
 // the second stage and the rows of t + 2 are in flight.  Both products use the 32x32x16 MFMA:
 //   S^T = K Q^T   lane (query = lane % 32, hh = lane / 32) register v holds the logit of key 8 (v / 4) + 4 hh + v % 4,
 //                 so a query's 32 logits sit in two lanes and the row maximum costs one cross-lane exchange;
@@ -971,8 +971,6 @@ template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
-constexpr int kRefreshWaves = 8;                        // wavefronts per workgroup of the refresh kernel, 32 queries each
-constexpr int kRefreshQueries = 32 * kRefreshWaves;  // queries per workgroup
 
 // A operand of O^T += V^T P^T (32x32x16) for d tile `dt` and k-step `ks`: lane (dcol = lane % 32, hh) needs
 // V[16 ks + 8 (e / 4) + 4 hh + e % 4][32 dt + dcol], e = 0..7 — two transposed reads of four consecutive rows each.
@@ -1001,13 +999,13 @@ __device__ __forceinline__ bf16x8 read_v_operand32(const char* stageV, int dt, i
   return __builtin_bit_cast(bf16x8, both);
 }
 
-template <int D>
-__global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(const RefreshArgs p) {
+template <int D, int NQ, int WAVES>  // NQ: 32-query tiles per wavefront; WAVES: wavefronts per workgroup
+__global__ __launch_bounds__(64 * WAVES, NQ == 1 ? 2 : 1) void refresh_attn_kernel(const RefreshArgs p) {
   using G = Geo<D>;
   constexpr int kKS = D / 16;                    // k-steps of K Q^T
   constexpr int kDT = D / 32;                    // 32-wide d tiles of V^T P^T
   constexpr int kBufBytes = 2 * G::kStageBytes;  // K stage + V stage of one sub-tile
-  constexpr int kShare = kRefreshWaves / 2;      // wavefronts that share the K (or the V) rows of a sub-tile
+  constexpr int kShare = WAVES / 2;              // wavefronts that share the K (or the V) rows of a sub-tile
   constexpr int NL = G::kLoads / kShare;         // loads per wavefront and sub-tile
   static_assert(G::kLoads % kShare == 0 && NL >= 1, "every wavefront stages at least one load");
   __shared__ __attribute__((aligned(16))) char stage[2][kBufBytes];
@@ -1023,12 +1021,12 @@ __global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(con
   const int work = (int)(blockIdx.x & 7u) * chunk + (int)(blockIdx.x >> 3);
   if (work >= p.n_work) return;  // whole workgroup
   const int h = work / p.n_qb;
-  const int q_row = (work - h * p.n_qb) * kRefreshQueries + wave * 32 + qi;
+  const int q_row0 = (work - h * p.n_qb) * (32 * NQ * WAVES) + wave * (32 * NQ) + qi;  // tile n: q_row0 + 32 n
   const int n_tiles = (p.L + kSubTile - 1) / kSubTile;
   const int n_full = p.L / kSubTile;
 
-  // this wavefront's share of every sub-tile: wavefronts 0, 1 the two halves of the K rows, 2, 3 of the V rows.
-  // Row addresses: a scalar base that moves by 32 rows per sub-tile plus per-lane byte offsets fixed for the launch.
+  // this wavefront's share of every sub-tile: the first half of the wavefronts split the K rows, the second half the
+  // V rows.  Row addresses: a scalar base that moves by 32 rows per sub-tile plus per-lane byte offsets fixed for the launch.
   const bool is_v = wave >= kShare;
   const int first = (wave % kShare) * NL;
   const char* src = reinterpret_cast<const char*>(is_v ? p.V + (int64_t)h * p.vsh : p.K + (int64_t)h * p.ksh);
@@ -1059,7 +1057,7 @@ __global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(con
   // work with nothing in front of it) while the vector ALU turns the logits of sub-tile t into probabilities, then
   // multiplies those with V sub-tile t.  K sub-tile j lives in K stage j % 2, V sub-tile j in V stage j % 2.
   // The loop is unrolled by two so that every stage index is a compile-time constant (an LDS address is then a
-  // register fixed for the launch plus an immediate); -1: taken from the sub-tile number at run time.
+  // register fixed for the launch plus an immediate).
   const int lead = is_v ? 0 : 1;
   char* my_stage = stage[0] + (is_v ? G::kStageBytes : 0) + first * 1024 + lane * 16;
   auto store = [&](int j) {  // this wavefront's rows of sub-tile j (in r) to stage j % 2
@@ -1074,32 +1072,28 @@ __global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(con
     }
   };
   fetch(0);
-  bf16x8 q[kKS];  // B operand of K Q^T: lane (query, hh) holds Q[query][16 ks + 8 hh .. + 7]
-  {
+  bf16x8 q[NQ][kKS];  // B operand of K Q^T: lane (query, hh) holds Q[query][16 ks + 8 hh .. + 7]
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const int q_row = q_row0 + 32 * n;
     const uint16_t* qsrc = p.Q + (int64_t)h * p.qsh + (int64_t)min(q_row, p.n_q - 1) * p.qsn + hh * 8;
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
       const uint4 v = *reinterpret_cast<const uint4*>(qsrc + ks * 16);
-      q[ks] = as_bf16x8(q_row < p.n_q ? v : make_uint4(0u, 0u, 0u, 0u));
+      q[n][ks] = as_bf16x8(q_row < p.n_q ? v : make_uint4(0u, 0u, 0u, 0u));
     }
   }
-  auto qk = [&](const char* sK) {
-    floatx16 acc;
+  float m_run[NQ], l_run[NQ];  // l_run: this lane's share of the row sum (its 16 of every 32 keys)
+  floatx16 o[NQ][kDT];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int n = 0; n < NQ; ++n) {
+    m_run[n] = -INFINITY;
+    l_run[n] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) {
-      const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(sK + stage_off<D>(qi, 2 * ks + hh)));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[ks], acc, 0, 0, 0);
-    }
-    return acc;
-  };
-  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's share of the row sum (its 16 of every 32 keys)
-  floatx16 o[kDT];
+    for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-  for (int dt = 0; dt < kDT; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+      for (int v = 0; v < 16; ++v) o[n][dt][v] = 0.f;
+  }
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   // scaled row maximum of one sub-tile's logits.  Slots past the end of a ragged sub-tile hold copies of its last
   // row, so they cannot raise the maximum and need no masking here.
@@ -1110,38 +1104,14 @@ __global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(con
     const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
     return fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
   };
-  auto rescale = [&](float mx) {
-    if (__ballot(mx > m_run) != 0ull) {  // some running maximum of this wavefront moves (rare after the first sub-tiles)
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first sub-tile (m_run = -inf, m_new finite)
-      m_run = m_new;
-      l_run *= alpha;
+  auto rescale = [&](int n, float mx) {
+    if (__ballot(mx > m_run[n]) != 0ull) {  // some running maximum of this wavefront moves (rare after the first sub-tiles)
+      const float m_new = fmaxf(m_run[n], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[n] - m_new);  // 0 on the first sub-tile (m_run = -inf, m_new finite)
+      m_run[n] = m_new;
+      l_run[n] *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < kDT; ++dt) o[dt] *= alpha;
-    }
-  };
-  // logits -> packed bf16 probabilities of the first n_valid key slots (0 for the rest); adds them to the running sum
-  auto probabilities = [&](const floatx16& a, uint32_t (&pk)[8], int n_valid) {
-#pragma unroll
-    for (int v = 0; v < 16; v += 2) {
-      float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[v], p.scale_log2, -m_run));
-      float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[v + 1], p.scale_log2, -m_run));
-      if (n_valid < kSubTile) {
-        const int key = 8 * (v >> 2) + 4 * hh + (v & 3);
-        p0 = key < n_valid ? p0 : 0.f;
-        p1 = key + 1 < n_valid ? p1 : 0.f;
-      }
-      pk[v >> 1] = cvt_pk_bf16(p0, p1);
-      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v >> 1]), ones, l_run, false);
-    }
-  };
-  auto pv = [&](const char* sV, const uint32_t (&pk)[8]) {
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8 pb = as_bf16x8(make_uint4(pk[4 * ks], pk[4 * ks + 1], pk[4 * ks + 2], pk[4 * ks + 3]));
-#pragma unroll
-      for (int dt = 0; dt < kDT; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand32<D>(sV, dt, ks, lane), pb, o[dt], 0, 0, 0);
+      for (int dt = 0; dt < kDT; ++dt) o[n][dt] *= alpha;
     }
   };
 
@@ -1151,104 +1121,158 @@ __global__ __launch_bounds__(64 * kRefreshWaves, 2) void refresh_attn_kernel(con
     if (1 < n_tiles) fetch(1);
   }
   __syncthreads();
-  floatx16 acc = qk(stage[0]);
-  float mx = row_max(acc);
+  floatx16 acc[NQ];
+  float mx[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+  }
+#pragma unroll
+  for (int ks = 0; ks < kKS; ++ks) {
+    const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(stage[0] + stage_off<D>(qi, 2 * ks + hh)));
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[n][ks], acc[n], 0, 0, 0);
+  }
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) mx[n] = row_max(acc[n]);
   stage_next(-1);
 
-  // One iteration, written as NS slots of one MFMA each — K Q^T of sub-tile t + 1 first, then V^T P^T of sub-tile t —
-  // with scheduling fences between the slots: a wavefront issues in order, so the vector work of the other sub-tile
-  // (exponentials of sub-tile t beside the K Q^T MFMAs, the row maximum of sub-tile t + 1 beside the last V^T P^T
-  // MFMAs) has to sit between the MFMAs in program order or it would wait behind all of them.  The LDS operand of slot
-  // s + kLead is requested in slot s.
-  auto body = [&](int t, auto which) {  // t + 1 < n_tiles: sub-tile t is full
-    constexpr int W = decltype(which)::value;
-    constexpr int NS = kKS + 2 * kDT;  // MFMAs per iteration
+  // One iteration, written as NS slots of one LDS operand and NQ MFMAs each — K Q^T of sub-tile t + 1 first, then
+  // V^T P^T of sub-tile t — with scheduling fences between the slots: a wavefront issues in order, so the vector work
+  // of the other sub-tile (exponentials of sub-tile t beside the K Q^T MFMAs, the row maximum of sub-tile t + 1 beside
+  // the last V^T P^T MFMAs) has to sit between the MFMAs in program order or it would wait behind all of them.  The
+  // LDS operand of slot s + kLead is requested in slot s.  n_valid < 32 only in the last iteration (kLast), which has no
+  // K Q^T part.
+  auto body = [&](int t, auto which, auto last_tag, int n_valid) {
+    constexpr int W = decltype(which)::value;     // stage of V sub-tile t (K sub-tile t + 1 sits in the other one); -1: t % 2
+    constexpr bool kLast = decltype(last_tag)::value;
+    constexpr int NS = kKS + 2 * kDT;             // operand slots per iteration
+    constexpr int S0 = kLast ? kKS : 0;           // first slot of this iteration
     constexpr int kLead = 3;
-    constexpr int kPer = 16 / kKS;     // logits turned into probabilities per K Q^T slot
+    constexpr int kPer = 16 / kKS;                // logits turned into probabilities per K Q^T slot and query tile
     __syncthreads();  // K sub-tile t + 1 and V sub-tile t are staged; everyone is done with iteration t - 1
-    rescale(mx);
-    const char* sK = stage[1 - W];
-    const char* sV = stage[W] + G::kStageBytes;
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) rescale(n, mx[n]);
+    const int w = W >= 0 ? W : (t & 1);
+    const char* sK = stage[1 - w];
+    const char* sV = stage[w] + G::kStageBytes;
     bf16x8 op[NS];
     auto read_op = [&](auto sc) {
-      constexpr int s = decltype(sc)::value;
+      constexpr int s = decltype(sc)::value + S0;
       if constexpr (s < kKS)
         op[s] = as_bf16x8(*reinterpret_cast<const uint4*>(sK + stage_off<D>(qi, 2 * s + hh)));
-      else
+      else if constexpr (s < NS)
         op[s] = read_v_operand32<D>(sV, (s - kKS) % kDT, (s - kKS) / kDT, lane);
     };
-    floatx16 next;
+    floatx16 next[NQ];
+    uint32_t pk[NQ][8];
+    float mxn[NQ];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) next[v] = 0.f;
-    uint32_t pk[8];
-    float mxn = 0.f;
+    for (int n = 0; n < NQ; ++n) {
+      mxn[n] = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) next[n][v] = 0.f;
+    }
+    auto probabilities = [&](int n, int v0, int v1) {  // logits v0 .. v1 - 1 of query tile n -> packed bf16, added to the row sum
+#pragma unroll
+      for (int v = v0; v < v1; v += 2) {
+        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[n][v], p.scale_log2, -m_run[n]));
+        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[n][v + 1], p.scale_log2, -m_run[n]));
+        if (kLast) {  // a ragged sub-tile: slots past the end count for nothing
+          const int key = 8 * (v >> 2) + 4 * hh + (v & 3);
+          p0 = key < n_valid ? p0 : 0.f;
+          p1 = key + 1 < n_valid ? p1 : 0.f;
+        }
+        pk[n][v >> 1] = cvt_pk_bf16(p0, p1);
+        l_run[n] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[n][v >> 1]), ones, l_run[n], false);
+      }
+    };
+    if (kLast) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) probabilities(n, 0, 16);
+    }
     static_for<kLead>(read_op);
     __builtin_amdgcn_sched_barrier(0);
-    static_for<NS>([&](auto sc) {
-      constexpr int s = decltype(sc)::value;
-      if constexpr (s + kLead < NS) read_op(std::integral_constant<int, s + kLead>{});
+    static_for<NS - S0>([&](auto sc) {
+      constexpr int s = decltype(sc)::value + S0;
+      if constexpr (s + kLead < NS) read_op(std::integral_constant<int, s + kLead - S0>{});
       if constexpr (s < kKS) {
-        next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], q[s], next, 0, 0, 0);
 #pragma unroll
-        for (int v = s * kPer; v < (s + 1) * kPer; v += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], p.scale_log2, -m_run));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v + 1], p.scale_log2, -m_run));
-          pk[v >> 1] = cvt_pk_bf16(p0, p1);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v >> 1]), ones, l_run, false);
+        for (int n = 0; n < NQ; ++n) {
+          next[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], q[n][s], next[n], 0, 0, 0);
+          probabilities(n, s * kPer, (s + 1) * kPer);
         }
       } else {
         constexpr int ks = (s - kKS) / kDT, dt = (s - kKS) % kDT;
-        const bf16x8 pb = as_bf16x8(make_uint4(pk[4 * ks], pk[4 * ks + 1], pk[4 * ks + 2], pk[4 * ks + 3]));
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], pb, o[dt], 0, 0, 0);
-        if constexpr (s == NS - 2) {  // row maximum of sub-tile t + 1: the in-lane part
-          mxn = fmaxf(next[0], next[1]);
 #pragma unroll
-          for (int v = 2; v < 16; ++v) mxn = fmaxf(mxn, next[v]);
+        for (int n = 0; n < NQ; ++n) {
+          const bf16x8 pb = as_bf16x8(make_uint4(pk[n][4 * ks], pk[n][4 * ks + 1], pk[n][4 * ks + 2], pk[n][4 * ks + 3]));
+          o[n][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[s], pb, o[n][dt], 0, 0, 0);
         }
-        if constexpr (s == NS - 1) {  // ... and the exchange between the two lanes of a query
-          const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mxn), __float_as_uint(mxn), false, false);
-          mxn = fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
+        if constexpr (!kLast && s == NS - 2) {  // row maximum of sub-tile t + 1: the in-lane part
+#pragma unroll
+          for (int n = 0; n < NQ; ++n) {
+            mxn[n] = fmaxf(next[n][0], next[n][1]);
+#pragma unroll
+            for (int v = 2; v < 16; ++v) mxn[n] = fmaxf(mxn[n], next[n][v]);
+          }
+        }
+        if constexpr (!kLast && s == NS - 1) {  // ... and the exchange between the two lanes of a query
+#pragma unroll
+          for (int n = 0; n < NQ; ++n) {
+            const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mxn[n]), __float_as_uint(mxn[n]), false, false);
+            mxn[n] = fmaxf(__uint_as_float(sw.x), __uint_as_float(sw.y)) * p.scale_log2;
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    mx = mxn;
-    stage_next(t);
-    acc = next;
+    if (!kLast) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        mx[n] = mxn[n];
+        acc[n] = next[n];
+      }
+      stage_next(t);
+    }
   };
   int t_body = 0;
   for (; t_body + 2 < n_tiles; t_body += 2) {  // straight-line pairs: no exit between the two halves
-    body(t_body, std::integral_constant<int, 0>{});
-    body(t_body + 1, std::integral_constant<int, 1>{});
+    body(t_body, std::integral_constant<int, 0>{}, std::false_type{}, kSubTile);
+    body(t_body + 1, std::integral_constant<int, 1>{}, std::false_type{}, kSubTile);
   }
-  if (t_body + 1 < n_tiles) body(t_body, std::integral_constant<int, 0>{});  // t_body is even
-  {  // last sub-tile (possibly ragged): its logits are in acc already
-    const int t = n_tiles - 1;
-    __syncthreads();
-    rescale(mx);
-    uint32_t pk[8];
-    probabilities(acc, pk, p.L - t * kSubTile);
-    pv(stage[t & 1] + G::kStageBytes, pk);
-  }
+  if (t_body + 1 < n_tiles) body(t_body, std::integral_constant<int, 0>{}, std::false_type{}, kSubTile);  // t_body is even
+  // last sub-tile (possibly ragged): its logits are in acc already
+  body(n_tiles - 1, std::integral_constant<int, -1>{}, std::true_type{}, p.L - (n_tiles - 1) * kSubTile);
 
   // lane (query, hh) register v of d tile dt holds O^T[32 dt + 8 (v / 4) + 4 hh + v % 4][query]: four consecutive
   // output columns per register quad.  The two lanes of a query add their halves of the row sum.
-  {
-    const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
-    l_run = __uint_as_float(sw.x) + __uint_as_float(sw.y);
-  }
-  if (q_row < p.n_q) {
-    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-    uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)q_row * p.osn + 4 * hh;
 #pragma unroll
-    for (int dt = 0; dt < kDT; ++dt)
+  for (int n = 0; n < NQ; ++n) {
+    const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[n]), __float_as_uint(l_run[n]), false, false);
+    const float l = __uint_as_float(sw.x) + __uint_as_float(sw.y);
+    const int q_row = q_row0 + 32 * n;
+    if (q_row < p.n_q) {
+      const float inv = l > 0.f ? 1.f / l : 0.f;
+      uint16_t* dst = p.out + (int64_t)h * p.osh + (int64_t)q_row * p.osn + 4 * hh;
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        *reinterpret_cast<uint2*>(dst + 32 * dt + 8 * j) =
-            make_uint2(cvt_pk_bf16(o[dt][4 * j] * inv, o[dt][4 * j + 1] * inv), cvt_pk_bf16(o[dt][4 * j + 2] * inv, o[dt][4 * j + 3] * inv));
-    if (p.lse && hh == 0)
-      p.lse[(int64_t)h * p.n_q + q_row] = l_run > 0.f ? (m_run + __builtin_amdgcn_logf(l_run)) * kLn2 : -INFINITY;
+      for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          *reinterpret_cast<uint2*>(dst + 32 * dt + 8 * j) = make_uint2(cvt_pk_bf16(o[n][dt][4 * j] * inv, o[n][dt][4 * j + 1] * inv),
+                                                                        cvt_pk_bf16(o[n][dt][4 * j + 2] * inv, o[n][dt][4 * j + 3] * inv));
+      if (p.lse && hh == 0) p.lse[(int64_t)h * p.n_q + q_row] = l > 0.f ? (m_run[n] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
   }
+}
+
+template <int D, int NQ, int WAVES>
+static hipError_t launch_refresh_t(RefreshArgs& a, const focus_shape& s, hipStream_t st) {
+  a.n_qb = ceil_div(s.n_gen, 32 * NQ * WAVES);
+  a.n_work = a.n_qb * s.n_heads;
+  hipLaunchKernelGGL((refresh_attn_kernel<D, NQ, WAVES>), dim3(8 * ceil_div(a.n_work, 8)), dim3(64 * WAVES), 0, st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, const focus_shape& s, void* out, float* lse,
@@ -1266,14 +1290,12 @@ hipError_t launch_refresh_attn(const void* Q, const void* K, const void* V, cons
   a.n_q = s.n_gen;
   a.L = s.n_ctx + s.n_resp;
   a.scale_log2 = kLog2e / sqrtf((float)s.head_dim);
-  a.n_qb = ceil_div(s.n_gen, kRefreshQueries);
-  a.n_work = a.n_qb * s.n_heads;
-  const dim3 grid(8 * ceil_div(a.n_work, 8));
-  if (s.head_dim == 128)
-    hipLaunchKernelGGL(refresh_attn_kernel<128>, grid, dim3(64 * kRefreshWaves), 0, st, a);
-  else
-    hipLaunchKernelGGL(refresh_attn_kernel<64>, grid, dim3(64 * kRefreshWaves), 0, st, a);
-  return hipGetLastError();
+  // Eight wavefronts of 32 queries: two per SIMD, and 256 queries share every staged sub-tile.  (Four wavefronts of 64
+  // queries — each LDS operand feeding two MFMAs, one wavefront per SIMD with 444 registers — gives the same sharing
+  // with half the LDS reads, but a lone wavefront cannot cover its own dependent vector-ALU chains: 0.82 against
+  // 1.01 PFLOP/s.)
+  if (s.head_dim == 128) return launch_refresh_t<128, 1, 8>(a, s, st);
+  return launch_refresh_t<64, 1, 8>(a, s, st);
 }
 
 // =====================================================================================================
