@@ -651,6 +651,36 @@ def test_cache_refresh_copies_every_row_and_emits_block_means(G, H, M, N, B, d):
     assert torch.equal(k_cache, k_new)
 
 
+def test_block_entry_then_step_uses_the_refreshed_cache_and_means(G):
+    """A block entry followed by a sparse step (Alg. 1): the caches are rewritten and K_bar formed in one pass, every
+    position attends densely over the new cache, and the next step's block scoring from those cached means picks the
+    same blocks, with the same scores bit for bit, as scoring from the raw keys."""
+    H, M, N, d, B, n_gen = 4, 4096, 64, 128, 64, 64
+    L = M + N
+    k_new, v_new = _rand_bf16(151, H, L, d).to(G.DEV), _rand_bf16(152, H, L, d).to(G.DEV)
+    k_cache, v_cache = torch.zeros_like(k_new), torch.zeros_like(v_new)
+    n_b = M // B
+    kbar = torch.empty(H, n_b, d, dtype=torch.float32, device=G.DEV)
+    q_all = _rand_bf16(153, H, L, d).to(G.DEV)
+    out_all = torch.empty_like(q_all)
+    fb.cache_refresh(k_cache, v_cache, fb.make_shape(q_all, k_cache, v_cache, M, B), k_new, v_new, kbar)
+    fb.refresh_attn(q_all, k_cache, v_cache, fb.make_shape(q_all, k_cache, v_cache, M, B, out_all), out_all, None)
+    torch.cuda.synchronize()
+    rows = np.array([0, 77, M - 1, M, L - 1])
+    ref, _ = fo.sparse_attention(G.to_np(q_all), rows, G.to_np(k_new), G.to_np(v_new), np.arange(M), M)
+    G.assert_attention_close(out_all[:, rows], ref)
+    # the following step: queries of the generation block, scoring from the cached means against scoring from raw K
+    q = q_all[:, M:M + n_gen].contiguous()
+    conf = np.random.default_rng(154).random(n_gen).astype(np.float32)
+    focus, active, counts = G.gpu_select(conf, None, 16, 0, 0, n_gen)
+    s_raw, kept_raw = G.gpu_block_scores(q, focus, counts, k_cache, None, M, B, 6)
+    s_mean, kept_mean = G.gpu_block_scores(q, focus, counts, None, kbar, M, B, 6)
+    assert torch.equal(s_raw, s_mean) and torch.equal(kept_raw, kept_mean)
+    R = fo.block_relevance(G.to_np(q), fo.select_focus(conf, None, 16), fo.block_means(G.to_np(k_new), M, B))
+    assert np.allclose(s_mean.cpu().numpy(), R, atol=2e-6)
+    assert kept_mean.cpu().tolist() == fo.top_indices(R, 6).tolist()
+
+
 # ------------------------------------------------------------------------------------------------ around the step
 @pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
 def test_token_confidence(G, n_rows, vocab, pad):
