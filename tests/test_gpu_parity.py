@@ -515,6 +515,65 @@ def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
         assert all(torch.equal(a, b["out"]) for a, b in zip(eager, st.bufs))
 
 
+# ------------------------------------------------------------------------------------------------ randomized shapes
+def _random_configs(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        H = int(rng.choice([1, 2, 3, 5]))
+        M = int(rng.integers(33, 3000))
+        N = int(rng.integers(0, 100))
+        B = int(rng.choice([16, 32, 48, 64, 100, 128]))
+        n_gen = int(rng.integers(1, 131))
+        n_act = int(rng.integers(1, min(n_gen, 80) + 1))
+        n_b = -(-M // B)
+        n_keep = int(rng.integers(0, n_b + 1)) if rng.random() < 0.3 else int(rng.integers(0, min(n_b, 12) + 1))
+        n_sink = int(rng.integers(0, min(M, 40) + 1))
+        out.append((H, M, N, d, B, n_gen, n_act, n_keep, n_sink))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_configs(64, 20260301), ids=lambda c: "-".join(map(str, c)))
+def test_randomized_shapes_against_the_oracle(G, cfg):
+    """Seeded random shapes (ragged everything, every query-tile count, zero kept blocks or sinks now and then): block
+    scores, sink scores and the attention over a random kept set, each against the oracle."""
+    H, M, N, d, B, n_gen, n_act, n_keep, n_sink = cfg
+    rng = np.random.default_rng(sum(cfg))
+    n_b = -(-M // B)
+    q, k, v = (_rand_bf16(161 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    focus = np.sort(rng.choice(active, max(1, n_act // 2), replace=False))
+    pad = min(2, n_gen - n_act)    # the capacity of the active list may not exceed n_gen
+    a_dev, f_dev = G.i32(list(active) + [-1] * pad), G.i32(list(focus) + [-1])
+    counts = G.i32([len(focus), n_act])
+    # block scores (values always; the Top-C only where no decision is a near-tie)
+    R_ref = fo.block_relevance(Q, focus, fo.block_means(K, M, B))
+    scores, kept_dev = G.gpu_block_scores(q, f_dev, counts, k, None, M, B, n_keep)
+    assert np.allclose(scores.cpu().numpy(), R_ref, atol=2e-6 * max(1.0, np.abs(R_ref).max()))
+    if 0 < n_keep < n_b and fo.decision_margin(R_ref, n_keep) > 1e-4:
+        assert kept_dev.cpu().tolist() == fo.top_indices(R_ref, n_keep).tolist()
+    # sink scores
+    S_ref = fo.sink_scores(Q, active, K)
+    col, sinks_dev = G.gpu_find_sinks(q, a_dev, counts, k, M, B, n_sink)
+    assert np.allclose(col.cpu().numpy(), S_ref, rtol=2e-4, atol=1e-9)
+    if 0 < n_sink < M and fo.decision_margin(S_ref, n_sink, np.arange(M + N) < M) > 1e-4:
+        assert sinks_dev.cpu().tolist() == fo.select_sinks(S_ref, M, n_sink).tolist()
+    # attention over a random kept set and random sinks (unsorted, with a repeat)
+    kept = rng.choice(n_b, n_keep, replace=False) if n_keep else np.zeros(0, dtype=np.int64)
+    sinks = rng.choice(M, n_sink, replace=False) if n_sink else np.zeros(0, dtype=np.int64)
+    if n_sink > 1:
+        sinks = np.concatenate([sinks, sinks[:1]])
+    out, lse = G.gpu_sparse_attn(q, a_dev, counts, k, v, M, B, G.i32(kept) if len(kept) else None, G.i32(sinks) if len(sinks) else None)
+    I_p = fo.attention_index_set(sinks, kept, M, B)
+    if len(I_p) + N == 0:
+        return   # nothing to attend to: covered by the dedicated empty-set test
+    ref, ref_lse = fo.sparse_attention(Q, active, K, V, I_p, M)
+    G.assert_attention_close(out[:, :n_act], ref)
+    assert np.allclose(lse.cpu().numpy()[:, :n_act], ref_lse, atol=2e-3)
+
+
 # ------------------------------------------------------------------------------------------------ grouped-query attention
 @pytest.mark.parametrize("H_kv,group,M,N,d,B,n_gen,k,window,n_keep,n_sink", [
     (2, 4, 2048, 32, 128, 64, 32, 6, 0, 5, 3),       # 24 query rows per K/V head: two query tiles
