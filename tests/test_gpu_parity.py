@@ -574,6 +574,57 @@ def test_randomized_shapes_against_the_oracle(G, cfg):
     assert np.allclose(lse.cpu().numpy()[:, :n_act], ref_lse, atol=2e-3)
 
 
+@pytest.mark.parametrize("cfg", _random_configs(32, 20260302), ids=lambda c: "-".join(map(str, c)))
+def test_randomized_shapes_fused_layer_probe_layer_and_block_entry(G, cfg):
+    """The same kind of seeded shapes through the fused calls: focus_sparse_layer against the oracle's layer (and bit
+    for bit against the separate calls), focus_probe_layer against the oracle's dense attention and sinks, and the two
+    block-entry calls against the oracle."""
+    H, M, N, d, B, n_gen, n_act, n_keep, n_sink = cfg
+    rng = np.random.default_rng(sum(cfg) + 1)
+    n_b, L = -(-M // B), M + N
+    n_keep = max(n_keep, 1)
+    q, k, v = (_rand_bf16(171 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, L, L)))
+    Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    focus = np.sort(rng.choice(active, max(1, n_act // 3), replace=False))
+    a_dev, f_dev, counts = G.i32(list(active)), G.i32(list(focus)), G.i32([len(focus), n_act])
+    # probe layer
+    out_p, lse_p, col, sinks_dev = G.gpu_probe_layer(q, a_dev, counts, k, v, M, B, n_sink)
+    S_ref = fo.sink_scores(Q, active, K)
+    assert np.allclose(col.cpu().numpy(), S_ref, rtol=2e-4, atol=1e-9)
+    ref_p, ref_lse_p = fo.sparse_attention(Q, active, K, V, np.arange(M), M)
+    G.assert_attention_close(out_p[:, :n_act], ref_p)
+    assert np.allclose(lse_p.cpu().numpy()[:, :n_act], ref_lse_p, atol=2e-3)
+    sinks_ref = fo.select_sinks(S_ref, M, n_sink)
+    sure_sinks = not (0 < n_sink < M) or fo.decision_margin(S_ref, n_sink, np.arange(L) < M) > 1e-4
+    if sure_sinks:
+        assert sinks_dev.cpu().tolist() == sinks_ref.tolist()
+    # fused sparse layer with the device's sinks
+    scores, kept, out, lse = G.gpu_sparse_layer(q, f_dev, a_dev, counts, k, v, None, M, B, n_keep, sinks_dev if n_sink else None)
+    s2, k2 = G.gpu_block_scores(q, f_dev, counts, k, None, M, B, n_keep)
+    o2, l2 = G.gpu_sparse_attn(q, a_dev, counts, k, v, M, B, k2, sinks_dev if n_sink else None)
+    assert torch.equal(scores, s2) and torch.equal(kept, k2) and torch.equal(out[:, :n_act], o2[:, :n_act])
+    lay = fo.focus_layer(Q, K, V, focus, active, np.array(sinks_dev.cpu().tolist(), dtype=np.int64), M, B, n_keep)
+    if n_keep == n_b or fo.decision_margin(lay["R"], n_keep) > 1e-4:
+        assert kept.cpu().tolist() == lay["blocks"].tolist()
+        G.assert_attention_close(out[:, :n_act], lay["out"])
+    # block entry: cache rewrite + block means, then every position attends to every key
+    k_cache, v_cache = torch.zeros_like(k), torch.zeros_like(v)
+    kbar = torch.empty(H, n_b, d, dtype=torch.float32, device=G.DEV)
+    fb.cache_refresh(k_cache, v_cache, fb.make_shape(q, k_cache, v_cache, M, B), k, v, kbar)
+    q_all = _rand_bf16(175, H, L, d).to(G.DEV)
+    out_all = torch.empty_like(q_all)
+    lse_all = torch.empty(H, L, dtype=torch.float32, device=G.DEV)
+    fb.refresh_attn(q_all, k_cache, v_cache, fb.make_shape(q_all, k_cache, v_cache, M, B, out_all), out_all, lse_all)
+    torch.cuda.synchronize()
+    assert torch.equal(k_cache, k) and torch.equal(v_cache, v)
+    assert np.allclose(kbar.cpu().numpy(), fo.block_means(K, M, B), rtol=1e-5, atol=1e-5)
+    rows = np.unique(rng.integers(0, L, 24))
+    ref_all, ref_lse_all = fo.sparse_attention(G.to_np(q_all), rows, K, V, np.arange(M), M)
+    G.assert_attention_close(out_all[:, rows], ref_all)
+    assert np.allclose(lse_all.cpu().numpy()[:, rows], ref_lse_all, atol=2e-3)
+
+
 # ------------------------------------------------------------------------------------------------ grouped-query attention
 @pytest.mark.parametrize("H_kv,group,M,N,d,B,n_gen,k,window,n_keep,n_sink", [
     (2, 4, 2048, 32, 128, 64, 32, 6, 0, 5, 3),       # 24 query rows per K/V head: two query tiles
