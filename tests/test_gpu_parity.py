@@ -207,6 +207,23 @@ def test_find_sinks_selection_is_exact_with_many_exact_ties(G, M, N, n_sink):
     assert np.allclose(S, Sref, rtol=2e-4, atol=1e-9)
 
 
+def test_find_sinks_many_sinks_with_an_unaligned_score_buffer(G):
+    """The bound-then-select path reads the column masses with 16-byte loads; a caller's score buffer that is only
+    4-byte aligned takes the radix select instead and must give the same sinks."""
+    H, M, N, d, n_gen, n_sink = 2, 8192, 32, 64, 16, 80
+    q, k = _rand_bf16(181, H, n_gen, d).to(G.DEV), _rand_bf16(182, H, M + N, d).to(G.DEV)
+    active = G.i32([0, 3, 5, 9])
+    col, sinks = G.gpu_find_sinks(q, active, None, k, M, 64, n_sink)
+    s = fb.make_shape(q, k, None, M, 64)
+    buf = torch.empty(M + N + 1, dtype=torch.float32, device=G.DEV)
+    col2, sinks2 = buf[1:], G.i32(None, n_sink)
+    assert col2.data_ptr() % 16 == 4
+    fb.find_sinks(q, active, None, k, s, n_sink, col2, sinks2, G.ws(fb.workspace_bytes(fb.FN_FIND_SINKS, s, active.numel())))
+    torch.cuda.synchronize()
+    assert torch.equal(col, col2) and torch.equal(sinks, sinks2)
+    assert sinks.cpu().tolist() == fo.select_sinks(col.cpu().numpy().astype(np.float64), M, n_sink).tolist()
+
+
 # ------------------------------------------------------------------------------------------------ stage 3
 def _attn_case(G, H, M, N, d, B, n_gen, active, kept, sinks, seed=11, counts=None, cap=None):
     q, k, v = (_rand_bf16(seed + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
