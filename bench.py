@@ -139,7 +139,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="stack32k", choices=["stack32k", "ctx32k", "ctx16k", "ctx8k", "tiny", "paper32k", "paper32k_gen256"])
+    ap.add_argument("--workload", default="stack32k", choices=["stack32k", "ctx32k", "ctx16k", "ctx8k", "tiny", "paper32k", "paper32k_gen256", "ctx128k"])
     ap.add_argument("--sets", type=int, default=2, help="independent copies of the layer tensors rotated between steps "
                     "so that no step finds its K/V in the 256 MB Infinity Cache")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call eagerly instead of replaying a HIP graph")

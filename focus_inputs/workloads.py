@@ -100,7 +100,11 @@ PAPER32K = Workload(name="paper32k", n_layers=1, n_heads=32, head_dim=128, n_ctx
 PAPER32K_GEN256 = PAPER32K.with_(name="paper32k_gen256", n_resp=256, n_gen=32, seed=_BASE_SEED + 6,
                                  sink_positions=_seeded_sinks(_BASE_SEED + 6, 32768, 4))
 
-WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K, PAPER32K, PAPER32K_GEN256)}
+# Four times the longest measured context: not a timed configuration; checks that nothing in the path is tied to 32K
+# (block counts, the limits of the small-N_sink tournament, index widths).
+CTX128K = _mk_single("ctx128k", 7, 131072, 0.03)
+
+WORKLOADS = {w.name: w for w in (TINY, CTX8K, CTX16K, CTX32K, STACK32K, PAPER32K, PAPER32K_GEN256, CTX128K)}
 
 
 def strong_sinks(w: Workload, logit_shift: float = 6.0) -> Workload:

@@ -412,10 +412,12 @@ def test_sparse_layer_equals_block_scores_then_sparse_attn(G, H, M, N, d, B, n_g
 
 
 # ------------------------------------------------------------------------------------------------ whole layer on the workloads
-@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx16k", "ctx32k", "paper32k", "paper32k_gen256"])
+@pytest.mark.parametrize("name", ["tiny", "ctx8k", "ctx16k", "ctx32k", "paper32k", "paper32k_gen256", "ctx128k"])
 def test_workload_layer_end_to_end(G, name):
     w = fi.WORKLOADS[name]
-    q, k, v = (t.to(G.DEV) for t in fi.layer_qkv(w, 0))
+    # one realised tensor feeds both sides: generated on the host and uploaded, except for the 128K context, whose
+    # 1.6 G elements are generated on the device and downloaded for the oracle
+    q, k, v = (t.to(G.DEV) for t in fi.layer_qkv(w, 0, device=G.DEV if name == "ctx128k" else "cpu"))
     conf = fi.confidence(w)
     Q, K, V = G.to_np(q), G.to_np(k), G.to_np(v)
     # oracle
