@@ -718,6 +718,28 @@ def test_refresh_attn_equals_full_bidirectional_attention(G, H, M, N, d):
     assert np.allclose(lse.cpu().numpy(), lse2.cpu().numpy(), atol=1e-3)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_refresh_attn_running_maximum_keeps_moving(G, d):
+    """Keys grow along the key axis and the queries are large, so the row maxima rise in almost every sub-tile and the
+    softmax is close to one-hot: the rescale branch of the kernel runs all the way through, not only at the start."""
+    H, M, N = 3, 3000, 77
+    L = M + N
+    grow = (1.0 + 4.0 * torch.arange(L) / L).view(1, L, 1)
+    q = (_rand_bf16(191, H, L, d).float() * 2.0).to(torch.bfloat16).to(G.DEV)
+    k = (_rand_bf16(192, H, L, d).float() * grow).to(torch.bfloat16).to(G.DEV)
+    v = _rand_bf16(193, H, L, d).to(G.DEV)
+    out = torch.empty(H, L, d, dtype=torch.bfloat16, device=G.DEV)
+    lse = torch.empty(H, L, dtype=torch.float32, device=G.DEV)
+    fb.refresh_attn(q, k, v, fb.make_shape(q, k, v, M, 64, out), out, lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = fo.sparse_attention(G.to_np(q), np.arange(L), G.to_np(k), G.to_np(v), np.arange(M), M)
+    G.assert_attention_close(out, ref)
+    assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=1e-5, atol=2e-3)
+    # the same inputs through the step's attention kernel with every block kept
+    out2, _ = G.gpu_sparse_attn(q, G.i32(np.arange(L)), None, k, v, M, 64, G.i32(np.arange(-(-M // 64))), None)
+    G.assert_attention_close(out2, ref)
+
+
 def test_refresh_attn_full_size_sampled_rows(G):
     """The launch bench.py --full-refresh times (32 heads, 32768 + 64 keys, d = 128, every position a query), checked on
     sampled (head, row) pairs the oracle computes one by one."""
