@@ -832,6 +832,41 @@ def test_block_entry_then_step_uses_the_refreshed_cache_and_means(G):
     assert kept_mean.cpu().tolist() == fo.top_indices(R, 6).tolist()
 
 
+def test_block_entry_calls_replay_in_a_hip_graph(G):
+    """The block-entry calls and the group expansion enqueue kernels only, so they can be captured: three replays, the
+    outputs wiped in between, each equal to the eager result bit for bit."""
+    H, M, N, d, B, n_gen, group = 2, 1500, 36, 128, 64, 32, 3
+    L = M + N
+    k_new, v_new, q_all = (_rand_bf16(201 + i, H, L, d).to(G.DEV) for i in range(3))
+    k_cache, v_cache, out = torch.zeros_like(k_new), torch.zeros_like(v_new), torch.zeros_like(q_all)
+    kbar = torch.zeros(H, -(-M // B), d, dtype=torch.float32, device=G.DEV)
+    lse = torch.zeros(H, L, dtype=torch.float32, device=G.DEV)
+    focus, active, counts = G.gpu_select(np.random.default_rng(204).random(n_gen).astype(np.float32), None, 5, 2, 0, n_gen)
+    f2, a2, c2 = G.i32(None, group * focus.numel()), G.i32(None, group * active.numel()), G.i32(None, 2)
+    s_c = fb.make_shape(q_all, k_cache, v_cache, M, B)
+    s_a = fb.make_shape(q_all, k_cache, v_cache, M, B, out)
+
+    def enqueue():
+        fb.expand_groups(focus, active, counts, n_gen, group, f2, a2, c2)
+        fb.cache_refresh(k_cache, v_cache, s_c, k_new, v_new, kbar)
+        fb.refresh_attn(q_all, k_cache, v_cache, s_a, out, lse)
+
+    outputs = (f2, a2, c2, k_cache, v_cache, kbar, out, lse)
+    enqueue()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outputs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue()
+    for _ in range(3):
+        for t in outputs:
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(eager, outputs))
+
+
 # ------------------------------------------------------------------------------------------------ around the step
 @pytest.mark.parametrize("n_rows,vocab,pad", [(5, 1000, 0), (3, 8, 0), (4, 13, 3), (64, 126464, 0), (7, 131077, 11), (2, 40000, 8)])
 def test_token_confidence(G, n_rows, vocab, pad):
