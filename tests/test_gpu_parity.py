@@ -534,6 +534,28 @@ def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
         assert all(torch.equal(a, b["out"]) for a, b in zip(eager, st.bufs))
 
 
+@pytest.mark.parametrize("n_act,n_sink,n_keep", [(16, 4, 7), (28, 60, 40), (64, 327, 128), (112, 20, 16)])
+def test_results_are_bit_identical_from_run_to_run(G, n_act, n_sink, n_keep):
+    """Nothing in the path depends on the order in which workgroups or atomics happen to land: twelve runs of the probe
+    layer and the fused sparse layer (one, two and four query tiles per workgroup, several query groups) give the same
+    bits every time."""
+    H, M, N, d, B, n_gen = 8, 16384, 64, 128, 64, 128
+    q, k, v = (_rand_bf16(211 + i, H, r, d).to(G.DEV) for i, r in enumerate((n_gen, M + N, M + N)))
+    rng = np.random.default_rng(n_act)
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    focus = active[:: max(1, n_act // 8)]
+    a_dev, f_dev, counts = G.i32(list(active)), G.i32(list(focus)), G.i32([len(focus), n_act])
+    first = None
+    for _ in range(12):
+        out_p, lse_p, col, sinks = G.gpu_probe_layer(q, a_dev, counts, k, v, M, B, n_sink)
+        scores, kept, out, lse = G.gpu_sparse_layer(q, f_dev, a_dev, counts, k, v, None, M, B, n_keep, sinks)
+        got = [t.clone() for t in (out_p[:, :n_act], lse_p[:, :n_act], col, sinks, scores, kept, out[:, :n_act], lse[:, :n_act])]
+        if first is None:
+            first = got
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, got))
+
+
 # ------------------------------------------------------------------------------------------------ randomized shapes
 def _random_configs(n, seed):
     rng = np.random.default_rng(seed)
