@@ -23,8 +23,10 @@
  *
  * Conventions shared by every entry point
  *  - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.  The caller owns every
- *    buffer; the library allocates and frees nothing, keeps no state between calls, and scratch memory
- *    comes from the caller's `workspace` (size from focus_workspace_bytes()).
+ *    buffer; the library allocates and frees nothing, keeps no state between calls, reads no environment
+ *    variable, and scratch memory comes from the caller's `workspace` (size from focus_workspace_bytes()).
+ *    Launch shapes (how many key splits a shape gets) are fixed functions of the arguments, so results are
+ *    reproducible bit for bit from call to call.
  *  - Q is bf16 [H, n_gen, d]; K and V are bf16 [H, M+N, d] (rows 0..M-1 prompt, rows M..M+N-1 response);
  *    strides are in elements, the innermost (d) stride is 1, every row start must be 16-byte aligned
  *    (base pointers 16-byte aligned, row strides multiples of 8).
@@ -241,7 +243,7 @@ int focus_token_confidence(const void* logits, int64_t row_stride, const uint8_t
 size_t focus_token_confidence_workspace(int32_t n_rows, int32_t vocab);
 
 /*
- * Approximate KV cache update (Sec. 3, Eq. 3; Alg. 1 "Update KV Cache for indices in I_active"): the cache rows of
+ * Approximate KV cache update (Sec. 3, Eq. 3; the cache-update step that ends each layer of Alg. 1): the cache rows of
  * the refreshed positions take the newly computed states, every other row is left as it is.
  *   K_cache, V_cache [dev] bf16 [H, M+N, d], strides k_/v_stride_* of `shape`, updated in place
  *   K_new, V_new     [dev] bf16 [H, max_active, d] with strides new_stride_h / new_stride_n (elements, multiples of 8):

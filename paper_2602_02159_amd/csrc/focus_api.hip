@@ -26,12 +26,12 @@ static int launch_fail(const char* what, hipError_t e) {
 
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  if (!v || !*v) return dflt;
-  const int x = atoi(v);
-  return x > 0 ? x : dflt;
-}
+// Launch shapes (workgroups per launch the key axis is cut for).  Fixed constants: split counts decide workspace
+// sizes and the order in which partial results are merged, so they must not vary between calls.
+constexpr int kAttnGroups = 1024;        // one sub-tile per wavefront at the 3 % keep configurations
+constexpr int kAttnGroupsShared = 512;   // several query tiles per workgroup: two resident workgroups per compute unit
+constexpr int kAttnGroupsPipe = 256;     // many sub-tiles per wavefront: one resident workgroup per compute unit
+constexpr int kLogitGroups = 2048;       // probe-layer logits
 
 static void plan_queries(SplitPlan& p, int max_active) {
   p.q_tiles = ceil_div(max_active, kQTile);
@@ -49,14 +49,14 @@ static void plan_splits(SplitPlan& p, int n_heads, int target_groups) {
 }
 
 static void plan_attention_splits(SplitPlan& p, const focus_shape& s) {
-  plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS", 1024));
+  plan_splits(p, s.n_heads, kAttnGroups);
   // Many sub-tiles per wavefront (dense layers, alpha = 0.5) or several query tiles per workgroup (window-expanded
   // queries): fewer, longer workgroups with pipelined key loops.  One sub-tile per wavefront (the 3 % keep
   // configurations): nothing to overlap.
   if (p.q_tiles_per_group > 1) {
-    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_SHARED", 512));  // two resident workgroups per compute unit
-  } else if (p.per_split > kWavesPerGroup && env_int("FOCUS_ATTN_PIPE", 1) == 1) {
-    plan_splits(p, s.n_heads, env_int("FOCUS_ATTN_GROUPS_PIPE", 256));  // one resident workgroup per compute unit
+    plan_splits(p, s.n_heads, kAttnGroupsShared);
+  } else if (p.per_split > kWavesPerGroup) {
+    plan_splits(p, s.n_heads, kAttnGroupsPipe);
     p.pipelined = p.per_split > kWavesPerGroup;
   }
 }
@@ -81,7 +81,7 @@ SplitPlan plan_logits(const focus_shape& s, int max_active) {
   SplitPlan p;
   plan_queries(p, max_active);
   p.n_sub = ceil_div(s.n_ctx + s.n_resp, kSubTile);
-  plan_splits(p, s.n_heads, env_int("FOCUS_LOGIT_GROUPS", 2048));
+  plan_splits(p, s.n_heads, kLogitGroups);
   return p;
 }
 

@@ -1,11 +1,14 @@
-// The two MFMA kernels of the step, both built on v_mfma_f32_16x16x32_bf16 (64-lane wavefronts):
+// The three MFMA kernels (64-lane wavefronts):
 //
-//   sparse_attn_kernel  Eq. 8 + Eq. 9: gathers the kept blocks, the sinks and the response rows of K / V and
-//                       runs a split-KV online-softmax attention of the active queries over them.  The same kernel
-//                       with every row kept is the dense layer (probe layer, comparison, block-entry refresh).
-//   qk_logits_kernel    Eq. 6: scaled logits of the active queries against every key of the probe layer with the
-//                       per-split row maxima / sums of the softmax normaliser, or — second pass, for more than 16
-//                       queries — the probabilities summed over the queries.
+//   sparse_attn_kernel   Eq. 8 + Eq. 9: gathers the kept blocks, the sinks and the response rows of K / V and
+//                        runs a split-KV online-softmax attention of the active queries over them
+//                        (v_mfma_f32_16x16x32_bf16).  The same kernel with every row kept is the dense layer (probe
+//                        layer, dense comparison).
+//   refresh_attn_kernel  block entry (Alg. 1): dense attention of EVERY position over every key, the one MFMA-bound
+//                        launch of the method (v_mfma_f32_32x32x16_bf16; described where it is defined).
+//   qk_logits_kernel     Eq. 6: scaled logits of the active queries against every key of the probe layer with the
+//                        per-split row maxima / sums of the softmax normaliser, or — second pass, for more than 16
+//                        queries — the probabilities summed over the queries (16x16x32).
 //
 // Work decomposition.  The key axis of one head is cut into sub-tiles of 32 rows, staged in LDS with an XOR
 // swizzle (applied on the global side of the load) so that the operand reads are conflict free.  How a workgroup
@@ -33,19 +36,6 @@
 
 namespace focus {
 
-// Optional per-wave phase stamps for kernel tuning (never defined in the shipped build).
-#ifdef FOCUS_STAMPS
-__device__ long long* g_stamps;
-#define FOCUS_STAMP(i)                                                                                          \
-  do {                                                                                                          \
-    if ((threadIdx.x & 63) == 0)                                                                                \
-      g_stamps[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (i)] = \
-          (i) == 0 ? wall_clock64() : clock64();                                                                \
-  } while (0)
-#else
-#define FOCUS_STAMP(i)
-#endif
-
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -71,6 +61,13 @@ constexpr int kStreamPolicy = 2;
 
 // s_waitcnt vmcnt(0): every outstanding global load, LDS-direct ones included, has landed
 __device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt lgkmcnt(0): every LDS read of this wavefront has returned.  Placed before an LDS-direct load that
+// overwrites a stage the wavefront has just read: that write-after-read order is not covered by vmcnt, and the fence
+// keeps the compiler from moving the load above the wait.
+__device__ __forceinline__ void wait_lds_reads() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 // ---------------------------------------------------------------------------------------- sub-tiles
 // Which rows of K/V a sub-tile covers.  Wave-uniform.
@@ -172,11 +169,24 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
   return t;
 }
 
+// Row of K/V that staged slot `slot` of sub-tile t reads.  Every slot reads a row of the key set, also the slots that
+// hold no key (they are masked out of the softmax, but their V row still meets a zero probability in the PV product,
+// and 0 x inf would poison the output): past the end of a contiguous tile the tile's last valid row, for a dropped
+// sink the sub-tile's first valid sink.  `last` = highest valid slot.  Requires t.vmask != 0.
+__device__ __forceinline__ int subtile_row(const SubTile& t, int slot, int last, const int32_t* __restrict__ sink_idx,
+                                           int n_sink) {
+  if (t.kind == 0) return t.row0 + min(slot, last);
+  // wave-uniform branch; the index stays inside the list even for slots that hold no key
+  const int mine = sink_idx[min(t.row0 + slot, n_sink - 1)];
+  const int fallback = sink_idx[t.row0 + __builtin_ctz(t.vmask)];
+  return ((t.vmask >> slot) & 1u) ? mine : fallback;
+}
+
 // HBM -> LDS for one 32-row sub-tile of a [rows, D] bf16 matrix.  Lane l of load i supplies the 16 bytes that
 // land at stage + 1024 i + 16 l, i.e. position (l mod chunks) of staged row i * rows_per_load + l / chunks; with
 // the swizzle that position holds logical chunk (l mod chunks) ^ (row mod chunks).  No load is predicated: a
-// slot that holds no key reads a valid row instead (the last valid row of a contiguous tile, row 0 for a
-// dropped sink) and is masked out of the softmax.  Requires t.vmask != 0.
+// slot that holds no key reads another row of the key set instead (subtile_row) and is masked out of the softmax.
+// Requires t.vmask != 0.
 template <int D>
 __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
                                               const int32_t* __restrict__ sink_idx, int n_sink, char* stage, int lane) {
@@ -188,11 +198,7 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
 #pragma unroll
   for (int i = 0; i < G::kLoads; ++i) {
     const int slot = i * G::kRowsPerLoad + sub;
-    int row = t.row0 + min(slot, last);
-    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
-      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
-      row = ((t.vmask >> slot) & 1u) ? s : 0;
-    }
+    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, kStreamPolicy);
@@ -214,11 +220,7 @@ __device__ __forceinline__ void fetch_subtile(const uint16_t* __restrict__ base,
 #pragma unroll
   for (int i = 0; i < G::kLoads; ++i) {
     const int slot = i * G::kRowsPerLoad + sub;
-    int row = t.row0 + min(slot, last);
-    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
-      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
-      row = ((t.vmask >> slot) & 1u) ? s : 0;
-    }
+    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
   }
@@ -234,11 +236,7 @@ __device__ __forceinline__ void fetch_subtile_part(const uint16_t* __restrict__ 
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
     const int slot = (first + i) * G::kRowsPerLoad + sub;
-    int row = t.row0 + min(slot, last);
-    if (t.kind != 0) {  // wave-uniform; the index stays inside the list even for slots that hold no key
-      const int s = sink_idx[min(t.row0 + slot, n_sink - 1)];
-      row = ((t.vmask >> slot) & 1u) ? s : 0;
-    }
+    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
   }
@@ -533,8 +531,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   const int split = p.groups_first ? blockIdx.z : blockIdx.x, h = blockIdx.y, qg = p.groups_first ? blockIdx.x : blockIdx.z;
   const int qt = wave % QT, kg = wave / QT;
   const int q0 = (qg * QT + qt) * kQTile;  // first position in the active list of this wavefront's query tile
-  FOCUS_STAMP(0);
-  FOCUS_STAMP(1);
 
   const int slot = wave & (kWavesPerGroup - 1);  // QT = 1: the slot this wavefront owns
   char* stageK = ldsA + slot * kBufBytes;
@@ -552,7 +548,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     const int tid = threadIdx.x;
     float r = 0.f;
     if (tid < p.n_b) r = sum_partials(p.rel_part, p.H, p.n_b, tid);
-    FOCUS_STAMP(9);
     const int n_f = p.counts ? min(max(p.counts[0], 0), p.n_focus_max) : p.n_focus_max;
     r *= n_f > 0 ? 1.f / ((float)n_f * (float)p.H) : 0.f;
     auto keyfn = [=](int, uint32_t& key) -> bool {
@@ -560,7 +555,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       return true;
     };
     block_topk<kFusedMaxBlocks>(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);  // n_b <= 256 = blockDim.x
-    FOCUS_STAMP(10);
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
       if (p.scores_out && tid < p.n_b) p.scores_out[tid] = r;
       if (tid < p.n_keep) p.kept_out[tid] = kept_sh[tid];
@@ -646,7 +640,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       }
     }
   }
-  FOCUS_STAMP(2);
   bf16x8 q[1][G::kKSteps];
   load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
   const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
@@ -659,10 +652,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
 
   bool first = true;
   auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) {  // one staged sub-tile into the running softmax
-    FOCUS_STAMP(3);
     floatx4 acc[1][2];
     qk_subtile<D, 1>(acc, sK, q, lane);
-    FOCUS_STAMP(4);
     if (SPILL) {  // contiguous rows only (dense): key row = row0 + slot
       float* dst = p.logits_out + ((int64_t)h * p.dense_rows + row0) * 16 + c;
 #pragma unroll
@@ -679,7 +670,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] *= alpha;
     }
     const bf16x8 pb = pack_bf16x8(ps);
-    FOCUS_STAMP(5);
     // O^T[dcol][query] += V^T . P^T
 #pragma unroll
     for (int ct = 0; ct < G::kColTiles; ++ct) {
@@ -687,7 +677,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, o[ct], 0, 0, 0);
     }
     first = false;
-    FOCUS_STAMP(6);
   };
   auto no_tile = []() {
     SubTile e;
@@ -738,6 +727,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       if (st < st_end) {
         t = locate(st);
         if (t.vmask != 0u) {
+          wait_lds_reads();
           issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
           issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
         }
@@ -769,7 +759,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       if (st < st_end) step(mineB, mineA);
     }
   }
-  FOCUS_STAMP(7);
 
   // ---- merge the wavefronts that share a query tile through LDS (the stages are free by now)
   float* myO = reinterpret_cast<float*>(ldsA + wave * kMergeBytes);  // [16][D]
@@ -838,7 +827,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
           *reinterpret_cast<float2*>(p.part_ml + 2 * row) = make_float2(lsum > 0.f ? mmax : -INFINITY, lsum);
       }
     }
-    FOCUS_STAMP(8);
   }
 }
 
@@ -1393,6 +1381,7 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
     st += kWavesPerGroup;
     if (st < st_end) {
       t = tile_of(st);
+      wait_lds_reads();
       issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
     }
     if (MODE == 2) {

@@ -579,7 +579,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
   const int tid = threadIdx.x, lane = tid & 63;
   const int chunk = (((M + kTopkThreads - 1) / kTopkThreads) + 3) & ~3;  // <= kTopkRegKeys (launcher)
   const int c0 = min(tid * chunk, M), c1 = min(c0 + chunk, M);
-  TOPK_STAMP(0);
   const uint32_t nominee = tid < n_cand ? cand_keys[tid] : 0u;  // key + 1 of a nominee, 0 = none; n_cand <= 512
   float4 v[kTopkRegKeys / 4];
 #pragma unroll
@@ -605,7 +604,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
     rk[4 * r4 + 3] = i + 3 < c1 ? order_key(v[r4].w) + 1u : 0u;
   }
   __syncthreads();
-  TOPK_STAMP(1);
   if (tid < kWave) {  // a lower bound of the N_sink-th largest nominee key: bitwise search over ballot counts, 8 nominees per lane
     uint32_t kv[8];
     const uint4 k0 = reinterpret_cast<const uint4*>(sm.keys)[lane * 2], k1 = reinterpret_cast<const uint4*>(sm.keys)[lane * 2 + 1];
@@ -640,7 +638,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
       }
     }
     if (lane == 0) bound_sh = max(T, 1u);
-    TOPK_STAMP(2);
   }
   __syncthreads();
   const uint32_t bound = bound_sh;
@@ -649,7 +646,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
   for (int r = 0; r < kTopkRegKeys; ++r) mine += rk[r] >= bound;
   uint32_t n_clear;
   uint32_t pos = block_exclusive_scan(mine, sm.wsum, &n_clear);
-  TOPK_STAMP(3);
   if (n_clear <= (uint32_t)kTopkThreads) {  // uniform
     if (tid >= (int)n_clear) sm.keys[tid] = 0u;  // the nominee keys are no longer needed (everyone passed the scan's barriers)
 #pragma unroll
@@ -661,7 +657,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
       }
     }
     __syncthreads();
-    TOPK_STAMP(4);
     if (tid < kWave) {
       if (n_clear <= 256u)
         wave_topk<4, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
@@ -669,7 +664,6 @@ __global__ __launch_bounds__(kTopkThreads) void sink_select_kernel(const float* 
         wave_topk<8, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
       else
         wave_topk<16, true>(sm.keys, (int)n_clear, n_sink, sink_idx, nullptr, &sm.prefix, 0, cidx);
-      TOPK_STAMP(5);
     }
     return;
   }

@@ -54,13 +54,6 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ part, in
   return acc;
 }
 
-#ifdef FOCUS_TOPK_STAMPS
-__device__ long long g_topk_stamps[32];
-#define TOPK_STAMP(i) do { if (threadIdx.x == 0) g_topk_stamps[i] = clock64(); } while (0)
-#else
-#define TOPK_STAMP(i)
-#endif
-
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkRegKeys = 32;
 
@@ -265,7 +258,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
     total = block_topk_small<(MAXN > 0 ? MAXN : kTopkThreads)>(keyfn, n, k, out, flags, sm);
   } else {
     // ---- radix select; each thread owns the contiguous run [c0, c1)
-    TOPK_STAMP(0);
     const int chunk = (((n + nt - 1) / nt) + 3) & ~3;  // a multiple of 4, so runs start 16-byte aligned
     const int c0 = min(tid * chunk, n), c1 = min(c0 + chunk, n);
     const bool in_regs = chunk <= kTopkRegKeys;
@@ -299,7 +291,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       uint32_t key = 0;
       return (c0 + r < c1 && keyfn(c0 + r, key)) ? key + 1u : 0u;
     };
-    TOPK_STAMP(1);
     // candidates, and the AND / OR of their keys: digits in which every key agrees need no counting pass
     uint32_t nvalid_local = 0, k_and = 0xffffffffu, k_or = 0u;
     auto stat = [&](uint32_t key) {
@@ -333,7 +324,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
     __syncthreads();
     const uint32_t all_and = sm.hist[0], varying = sm.hist[0] ^ sm.hist[1];
     __syncthreads();
-    TOPK_STAMP(2);
     const uint32_t k_eff = min((uint32_t)max(k, 0), nvalid);
     uint32_t T = 0xffffffffu, need = 0;  // on key + 1; k_eff == 0: nothing is > T and nothing is needed
     if (k_eff > 0) {
@@ -344,7 +334,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
           maskbits |= 0xffu << shift;
           continue;
         }
-        TOPK_STAMP(3 + (24 - shift) / 8 * 2);
         if (tid < 256) sm.hist[tid] = 0;
         __syncthreads();
         // Histogram of this digit over the thread's run.  Equal digits that follow each other are merged into one
@@ -371,7 +360,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
         }
         if (run) atomicAdd(&sm.hist[cur], run);
         __syncthreads();
-        TOPK_STAMP(4 + (24 - shift) / 8 * 2);
         // suffix counts over the 256 digits: above[d] = number of matching keys whose digit exceeds d
         uint32_t mine = 0, incl = 0;
         if (tid < 256) {
@@ -403,7 +391,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       T = prefix;
       need = remaining;
     }
-    TOPK_STAMP(11);
     // ---- ordered compaction
     uint32_t cg = 0, ce = 0;
     if (in_regs) {
@@ -447,7 +434,6 @@ __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int3
       }
     }
     total = tg + min(te, need);
-    TOPK_STAMP(12);
   }
   for (int i = (int)total + tid; i < k; i += nt) out[i] = -1;
   if (tid == 0 && out_count) *out_count = (int32_t)total;

@@ -339,6 +339,32 @@ def test_sparse_attn_many_sinks_inside_and_outside_kept_blocks(G, n_act, ascendi
     assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
 
 
+@pytest.mark.parametrize("n_act", [9, 40])
+def test_sparse_attn_unattended_rows_may_hold_inf_or_nan(G, n_act):
+    """Rows outside I_p must not influence the result (Eq. 8, Eq. 9), whatever they hold: sink slots that hold no key
+    (dropped, repeated or out-of-range entries, padding) and the clamped slots of ragged tiles read some row of K / V,
+    and that row has to be one of the attended ones.  Every unattended row of K and V is filled with inf / NaN here."""
+    H, M, N, d, B, n_gen = 2, 1000, 21, 128, 48, 48
+    rng = np.random.default_rng(77 + n_act)
+    kept = [2, 7, 20]                                            # block 20 is the ragged last block (rows 960..999)
+    sinks = [5, 130, 131, 5, 2000, -1, 333, 98, 340]             # 130, 131, 98 and 340 lie in kept blocks; 5 twice; two invalid
+    active = np.sort(rng.choice(n_gen, n_act, replace=False))
+    q, k, v = (_rand_bf16(300 + i, H, r, d) for i, r in enumerate((n_gen, M + N, M + N)))
+    I_p = fo.attention_index_set(sinks, kept, M, B)
+    attended = np.zeros(M + N, bool)
+    attended[I_p] = True
+    attended[M:] = True
+    ref, ref_lse = fo.sparse_attention(G.to_np(q), active, G.to_np(k), G.to_np(v), I_p, M)
+    bad = torch.tensor(~attended)
+    k[:, bad] = float("inf")
+    v[:, bad] = float("nan")
+    v[:, 0] = float("inf")                                       # row 0 is not attended
+    assert not attended[0]
+    out, lse = G.gpu_sparse_attn(q.to(G.DEV), G.i32(active), None, k.to(G.DEV), v.to(G.DEV), M, B, G.i32(kept), G.i32(sinks))
+    G.assert_attention_close(out, ref)
+    assert np.allclose(lse.cpu().numpy(), ref_lse, atol=2e-3)
+
+
 # ------------------------------------------------------------------------------------------------ probe layer
 @pytest.mark.parametrize("H,M,N,d,B,n_gen,n_act,n_sink", [
     (4, 1024, 32, 64, 64, 32, 8, 2),          # the tiny shape: a single key split

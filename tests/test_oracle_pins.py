@@ -205,6 +205,25 @@ def test_sink_scores_key_shift_and_head_permutation_invariance():
     assert not np.allclose(fo.sink_scores(Q, [0, 5], K, pooled_query=True), S, atol=1e-6)
 
 
+def test_sink_scores_pooled_query_reading_by_loops():
+    # the other reading of Eq. 6 (kept for comparison only): per head ONE softmax of the mean active query
+    H, L, d = 2, 9, 4
+    Q, K = _rand(61, H, 5, d), _rand(62, H, L, d)
+    active = [1, 3, 4]
+    S = fo.sink_scores(Q, active, K, pooled_query=True)
+    ref = np.zeros(L)
+    for h in range(H):
+        qbar = [sum(Q[h, i, c] for i in active) / len(active) for c in range(d)]
+        logit = [sum(qbar[c] * K[h, j, c] for c in range(d)) / math.sqrt(d) for j in range(L)]
+        z = sum(math.exp(x) for x in logit)
+        for j in range(L):
+            ref[j] += math.exp(logit[j]) / z / H
+    assert np.allclose(S, ref, atol=1e-14)
+    assert S.sum() == pytest.approx(1.0, abs=1e-12)
+    # with a single active query the two readings coincide
+    assert np.allclose(fo.sink_scores(Q, [2], K, pooled_query=True), fo.sink_scores(Q, [2], K), atol=1e-15)
+
+
 # --------------------------------------------------------------------------- stage 3 (Eq. 8, Eq. 9)
 def test_attention_index_set_membership():
     M, B = 23, 8
