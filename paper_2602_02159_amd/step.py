@@ -25,10 +25,12 @@ class FocusStep:
     `logits` (bf16 [n_gen, vocab], optional): the step then starts with focus_token_confidence, whose output is the
     confidence the query selection ranks (`conf` is overwritten).
     `dense_tail`: the last so many layers attend to every block (the schedule that keeps the final layers dense).
+    `kbars` (optional, one fp32 [H, n_b, d] tensor per layer): block means the caller already holds — what
+    focus_cache_refresh emitted at the block entry — used by the cached-means stages instead of buffers of this object.
     """
 
     def __init__(self, conf, masked, probe, sparse_layers, n_ctx: int, block: int, k_focus: int, window: int, n_keep: int,
-                 n_sink: int, cached_means: bool = False, dense: bool = False, logits=None, dense_tail: int = 0):
+                 n_sink: int, cached_means: bool = False, dense: bool = False, logits=None, dense_tail: int = 0, kbars=None):
         q0 = probe[0]
         dev = q0.device
         self.H, self.n_gen, self.d = q0.shape
@@ -47,9 +49,9 @@ class FocusStep:
             "kept": i32(n_keep),
             "scores": torch.empty(self.n_b, dtype=torch.float32, device=dev),
             "out": torch.zeros((self.H, self.max_active, self.d), dtype=torch.bfloat16, device=dev),
-            "kbar": torch.empty((self.H, self.n_b, self.d), dtype=torch.float32, device=dev),
+            "kbar": kbars[i] if kbars is not None else torch.empty((self.H, self.n_b, self.d), dtype=torch.float32, device=dev),
             "partials": torch.empty((self.H, self.n_b), dtype=torch.float32, device=dev),
-        } for _ in self.layers]
+        } for i in range(len(self.layers))]
         self._keep = []  # shapes and workspaces referenced by raw pointers below
         L = fb.lib()
         p = lambda t: None if t is None else C.c_void_p(t.data_ptr())

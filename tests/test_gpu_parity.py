@@ -504,6 +504,68 @@ def test_stack_reuses_probe_layer_sinks(G):
         G.assert_attention_close(out, step["layers"][l]["out"])
 
 
+def test_stack32k_full_size_step_against_the_oracle(G):
+    """The 32-layer, 32K-context workload at full size, as bench.py times it: block means from the block-entry cache
+    refresh, query selection, sinks at layer 16, then layers 17..31 through focus_sparse_layer with those cached means.
+    Every layer's kept blocks bit-exact and output within tolerance of oracle.focus_step; the sink buffer is the same
+    after every layer; one HIP-graph replay of the whole step reproduces the eager bits."""
+    from paper_2602_02159_amd.step import FocusStep
+    w = fi.STACK32K
+    sparse_ids = list(range(w.first_sparse_layer, w.n_layers))
+    conf, masked = fi.confidence(w, G.DEV), fi.masked_all(w, G.DEV)
+    probe = fi.layer_qkv(w, w.probe_layer, G.DEV, which="qkv")
+    layers, kbars = [], []
+    for l in sparse_ids:                                         # block entry of layer l: cache and block means in one pass
+        q, k_new, v_new = fi.layer_qkv(w, l, G.DEV)
+        k_cache, v_cache = torch.empty_like(k_new), torch.empty_like(v_new)
+        kbar = torch.empty(w.n_heads, w.n_blocks, w.head_dim, dtype=torch.float32, device=G.DEV)
+        fb.cache_refresh(k_cache, v_cache, fb.make_shape(q, k_cache, v_cache, w.n_ctx, w.block), k_new, v_new, kbar)
+        torch.cuda.synchronize()
+        assert torch.equal(k_cache, k_new) and torch.equal(v_cache, v_new)
+        del k_new, v_new
+        layers.append((q, k_cache, v_cache))
+        kbars.append(kbar)
+    st = FocusStep(conf, masked, probe, layers, w.n_ctx, w.block, w.k_focus, w.window, w.n_keep, w.n_sink, cached_means=True,
+                   kbars=kbars)
+    # eager, one call at a time
+    st.issue("select")
+    st.issue("find_sinks")
+    torch.cuda.synchronize()
+    frozen = st.sink_idx.clone()
+    for i in range(len(layers)):
+        st.issue("sparse_layer_cached", i)
+        torch.cuda.synchronize()
+        assert torch.equal(st.sink_idx, frozen)                  # handed on unchanged (cross-layer reuse)
+    # oracle, one layer's tensors on the host at a time
+    tensors = {w.probe_layer: probe}
+    tensors.update({l: t for l, t in zip(sparse_ids, layers)})
+    ref = fo.focus_step(conf.cpu().numpy(), None, w.k_focus, w.window, 0, w.n_gen, lambda l: tuple(G.to_np(t) for t in tensors[l]),
+                        w.probe_layer, sparse_ids, w.n_ctx, w.block, w.n_keep, w.n_sink)
+    n_q = len(ref["active"])
+    assert st.counts.cpu().tolist() == [len(ref["focus"]), n_q]
+    assert st.focus_idx.cpu().tolist() == ref["focus"].tolist() and st.active_idx.cpu().tolist()[:n_q] == ref["active"].tolist()
+    assert fo.decision_margin(ref["S"], w.n_sink, np.arange(w.n_kv) < w.n_ctx) > 1e-4
+    assert frozen.cpu().tolist() == ref["sinks"].tolist()
+    for i, l in enumerate(sparse_ids):
+        lay = ref["layers"][l]
+        assert fo.decision_margin(lay["R"], w.n_keep) > 1e-4
+        assert st.bufs[i]["kept"].cpu().tolist() == lay["blocks"].tolist(), f"layer {l}"
+        assert np.allclose(st.bufs[i]["scores"].cpu().numpy(), lay["R"], atol=2e-6)
+        G.assert_attention_close(st.bufs[i]["out"][:, :n_q], lay["out"])
+    # the whole step as one graph, outputs wiped first
+    eager = [(b["out"].clone(), b["kept"].clone()) for b in st.bufs]
+    st.capture()
+    for b in st.bufs:
+        b["out"].zero_()
+        b["kept"].fill_(-3)
+    st.sink_idx.fill_(-3)
+    torch.cuda.synchronize()
+    st.run()
+    torch.cuda.synchronize()
+    assert torch.equal(st.sink_idx, frozen)
+    assert all(torch.equal(o, b["out"]) and torch.equal(kp, b["kept"]) for (o, kp), b in zip(eager, st.bufs))
+
+
 def test_step_driver_graph_with_confidence_probe_layer_and_dense_tail(G):
     """The whole step as the driver sequences it and a HIP graph replays it: confidence from logits, query selection,
     the probe layer's dense attention with the sinks as a by-product, sparse layers, and a dense last layer."""
