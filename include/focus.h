@@ -13,6 +13,7 @@
  *     focus_block_scores     per sparse layer                   -> R_b, B_relevant
  *     focus_sparse_attn      per sparse layer                   -> Attn
  *     focus_sparse_layer     = focus_block_scores + focus_sparse_attn of one layer, fused into fewer launches
+ *     focus_sparse_layer_static   the same without a caller workspace (built-in scratch array; allocates nothing)
  *     focus_probe_layer      = dense attention of the probe layer + focus_find_sinks, sharing the QK^T work
  *     focus_block_partials / focus_top_blocks   the two halves of focus_block_scores (head-sharded callers)
  *     focus_refresh_attn     dense attention of every position (block entry)
@@ -199,6 +200,23 @@ int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* a
                        const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink,
                        float* scores, int32_t* kept_blocks, void* out, float* lse, void* workspace, size_t ws_bytes,
                        void* stream);
+
+/*
+ * focus_sparse_layer for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture that has no pool of its own, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without
+ * workspace / ws_bytes), same kernels and bit-identical outputs; the scratch memory is an 8 MiB array built into the
+ * library's device code (each GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing.  Shapes whose scratch need (focus_workspace_bytes(FOCUS_FN_SPARSE_LAYER, ...)) exceeds
+ * 8 MiB are rejected with FOCUS_EWORKSPACE and nothing is enqueued — the 32K-context layer with 16 active queries
+ * needs 2.3 MB.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams,
+ * different host threads) race on it and must be serialised by the caller; calls on one stream are ordered by the
+ * stream.  Nothing is assumed about the array's previous contents.  The first call on a device looks the array's
+ * address up (with that device current) and should not be made under stream capture.
+ */
+int focus_sparse_layer_static(const void* Q, const int32_t* focus_idx, const int32_t* active_idx, const int32_t* counts,
+                              int32_t n_focus_max, int32_t max_active, const void* K, const void* V, const float* kbar,
+                              const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink,
+                              float* scores, int32_t* kept_blocks, void* out, float* lse, void* stream);
 
 /*
  * The probe layer in one call: a dense layer of Alg. 1 (l <= l_dense: every key is attended, queries restricted to

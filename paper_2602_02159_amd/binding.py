@@ -19,7 +19,7 @@ FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_ELAUNCH = 0,
 FN_BLOCK_SCORES, FN_FIND_SINKS, FN_SPARSE_ATTN, FN_SPARSE_LAYER, FN_PROBE_LAYER = 1, 2, 3, 4, 5
 
 EXPORTS = ("focus_select_queries", "focus_expand_groups", "focus_block_means", "focus_block_scores", "focus_find_sinks", "focus_sparse_attn",
-           "focus_sparse_layer", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn", "focus_cache_refresh",
+           "focus_sparse_layer", "focus_sparse_layer_static", "focus_block_partials", "focus_top_blocks", "focus_probe_layer", "focus_refresh_attn", "focus_cache_refresh",
            "focus_token_confidence", "focus_token_confidence_workspace", "focus_cache_update",
            "focus_workspace_bytes", "focus_helper_k", "focus_helper_n_keep", "focus_helper_n_sink", "focus_last_error",
            "focus_version")
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.focus_find_sinks.argtypes = [p, p, p, i32, p, sp, i32, p, p, p, sz, p]
         L.focus_sparse_attn.argtypes = [p, p, p, i32, p, p, sp, p, i32, p, i32, p, p, p, sz, p]
         L.focus_sparse_layer.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p, sz, p]
+        L.focus_sparse_layer_static.argtypes = [p, p, p, p, i32, i32, p, p, p, sp, i32, p, i32, p, p, p, p, p]
         L.focus_probe_layer.argtypes = [p, p, p, i32, p, p, sp, i32, p, p, p, p, p, sz, p]
         L.focus_refresh_attn.argtypes = [p, p, p, sp, p, p, p]
         L.focus_cache_refresh.argtypes = [p, p, sp, p, p, C.c_int64, C.c_int64, p, p]
@@ -68,7 +69,7 @@ def lib() -> C.CDLL:
         L.focus_block_partials.argtypes = [p, p, p, i32, p, p, sp, p, p]
         L.focus_top_blocks.argtypes = [p, i32, p, i32, i32, i32, p, p, p]
         for name in ("focus_select_queries", "focus_expand_groups", "focus_block_means", "focus_block_scores", "focus_find_sinks",
-                     "focus_sparse_attn", "focus_sparse_layer", "focus_block_partials", "focus_top_blocks",
+                     "focus_sparse_attn", "focus_sparse_layer", "focus_sparse_layer_static", "focus_block_partials", "focus_top_blocks",
                      "focus_probe_layer", "focus_refresh_attn", "focus_token_confidence", "focus_cache_update", "focus_cache_refresh"):
             getattr(L, name).restype = C.c_int
         L.focus_workspace_bytes.argtypes = [i32, sp, i32, i32, i32]
@@ -264,3 +265,16 @@ def sparse_layer(q, focus_idx, active_idx, counts, k, v, kbar, shape: Shape, n_k
                                     active_idx.numel(), _ptr(k), _ptr(v), _ptr(kbar), C.byref(shape), n_keep, _ptr(sink_idx),
                                     n_sink, _ptr(scores), _ptr(kept_blocks), _ptr(out), _ptr(lse), _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sparse_layer_static(q, focus_idx, active_idx, counts, k, v, kbar, shape: Shape, n_keep: int, sink_idx, n_sink: int, scores,
+                        kept_blocks, out, lse) -> None:
+    """focus_sparse_layer without a workspace argument: the library's built-in scratch array is used; nothing is allocated."""
+    _need(q, torch.bfloat16, "Q")
+    _need(k, torch.bfloat16, "K")
+    _need(v, torch.bfloat16, "V")
+    _need(out, torch.bfloat16, "out")
+    _check(lib().focus_sparse_layer_static(_ptr(q), _ptr(focus_idx), _ptr(active_idx), _ptr(counts), focus_idx.numel(),
+                                           active_idx.numel(), _ptr(k), _ptr(v), _ptr(kbar), C.byref(shape), n_keep,
+                                           _ptr(sink_idx), n_sink, _ptr(scores), _ptr(kept_blocks), _ptr(out), _ptr(lse),
+                                           _stream()))

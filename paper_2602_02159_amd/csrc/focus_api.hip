@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "focus_kernels.h"
 
@@ -196,6 +197,90 @@ static LayerWs ws_layer(const focus_shape& s, const SplitPlan& p) {
   w.attn = w.sc.total;
   w.total = w.attn + w.at.total;
   return w;
+}
+
+// ---- scratch memory for callers that cannot allocate (focus_sparse_layer_static) --------------------------------
+// One array per GPU, resident from the moment the library's code object is loaded on that GPU until the process ends.
+// In host code the array's name is only a stand-in: its device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what the kernels receive.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_addr[kMaxDevices];  // by device ordinal; nullptr = not looked up yet
+static std::mutex g_scratch_mutex;
+
+static int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer_static(hipGetDevice)", e);
+  if (dev < 0 || dev >= kMaxDevices) return fail(FOCUS_EUNSUPPORTED, "focus_sparse_layer_static: device ordinal %d not below %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_addr[dev] == nullptr) {  // first call on this device, which is the current one
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || ptr == nullptr) return launch_fail("focus_sparse_layer_static(hipGetSymbolAddress)", e);
+    g_scratch_addr[dev] = ptr;
+  }
+  *out = g_scratch_addr[dev];
+  return FOCUS_OK;
+}
+
+static int sparse_layer_impl(const char* who, const void* Q, const int32_t* focus_idx, const int32_t* active_idx,
+                             const int32_t* counts, int32_t n_focus_max, int32_t max_active, const void* K, const void* V,
+                             const float* kbar, const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx,
+                             int32_t n_sink, float* scores, int32_t* kept_blocks, void* out, float* lse, void* workspace,
+                             size_t ws_bytes, bool static_scratch, void* stream) {
+  if (int rc = check_shape(shape, true, true, true, true)) return rc;
+  if (!Q || !focus_idx || !active_idx || !K || !V || !out) return fail(FOCUS_EINVAL, "%s: NULL pointer", who);
+  const int n_b = ceil_div(shape->n_ctx, shape->block);
+  if (n_focus_max < 1 || n_focus_max > shape->n_gen) return fail(FOCUS_EINVAL, "%s: n_focus_max=%d not in [1, n_gen]", who, n_focus_max);
+  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "%s: max_active=%d not in [1, n_gen]", who, max_active);
+  if (n_keep < 0 || n_keep > n_b) return fail(FOCUS_EINVAL, "%s: n_keep=%d not in [0, n_b=%d]", who, n_keep, n_b);
+  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "%s: n_sink=%d not in [0, n_ctx]", who, n_sink);
+  if ((n_keep > 0 && !kept_blocks) || (n_sink > 0 && !sink_idx)) return fail(FOCUS_EINVAL, "%s: index array is NULL", who);
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || (kbar && !aligned16(kbar)))
+    return fail(FOCUS_EINVAL, "%s: pointers must be 16-byte aligned", who);
+  const SplitPlan p = plan_attention(*shape, max_active, n_keep, n_sink);
+  const LayerWs w = ws_layer(*shape, p);
+  if (static_scratch) {  // every argument has been checked by now: look the built-in array up (first call on a device) and use it
+    if (kStaticScratchBytes < w.total)
+      return fail(FOCUS_EWORKSPACE, "%s: this shape needs %zu bytes of scratch, the built-in array holds %zu; use focus_sparse_layer with a caller workspace",
+                  who, w.total, kStaticScratchBytes);
+    if (int rc = static_scratch_ptr(&workspace)) return rc;
+    ws_bytes = kStaticScratchBytes;
+  }
+  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
+    return fail(FOCUS_EWORKSPACE, "%s: workspace needs %zu bytes, 16-byte aligned", who, w.total);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* part = reinterpret_cast<float*>(ws + w.sc.part);
+  float* R = scores ? scores : reinterpret_cast<float*>(ws + w.sc.scores);
+  float* part_o = reinterpret_cast<float*>(ws + w.attn + w.at.part_o);
+  float* part_ml = reinterpret_cast<float*>(ws + w.attn + w.at.part_ml);
+  hipError_t e;
+  const bool fused = n_b <= kFusedMaxBlocks && n_keep > 0;
+  if (!kbar)
+    e = launch_block_means_relevance(K, Q, focus_idx, counts, n_focus_max, *shape, nullptr, part, st);
+  else
+    e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(relevance)", e);
+  if (fused) {
+    FusedTopC f;
+    f.rel_part = part;
+    f.scores_out = R;
+    f.kept_out = kept_blocks;
+    f.n_focus_max = n_focus_max;
+    e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, nullptr, n_keep, sink_idx, n_sink, p, out, lse,
+                           part_o, part_ml, &f, st);
+    if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
+    return FOCUS_OK;
+  }
+  e = launch_reduce_topk(part, shape->n_heads, counts, n_focus_max, R, n_b, n_keep, kept_blocks, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(top-C)", e);
+  e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, kept_blocks, n_keep, sink_idx, n_sink, p, out, lse,
+                         part_o, part_ml, nullptr, st);
+  if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
+  return FOCUS_OK;
 }
 
 }  // namespace focus
@@ -545,50 +630,16 @@ int focus_sparse_layer(const void* Q, const int32_t* focus_idx, const int32_t* a
                        int32_t n_focus_max, int32_t max_active, const void* K, const void* V, const float* kbar,
                        const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink, float* scores,
                        int32_t* kept_blocks, void* out, float* lse, void* workspace, size_t ws_bytes, void* stream) {
-  if (int rc = check_shape(shape, true, true, true, true)) return rc;
-  if (!Q || !focus_idx || !active_idx || !K || !V || !out) return fail(FOCUS_EINVAL, "focus_sparse_layer: NULL pointer");
-  const int n_b = ceil_div(shape->n_ctx, shape->block);
-  if (n_focus_max < 1 || n_focus_max > shape->n_gen) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_focus_max=%d not in [1, n_gen]", n_focus_max);
-  if (max_active < 1 || max_active > shape->n_gen) return fail(FOCUS_EINVAL, "focus_sparse_layer: max_active=%d not in [1, n_gen]", max_active);
-  if (n_keep < 0 || n_keep > n_b) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_keep=%d not in [0, n_b=%d]", n_keep, n_b);
-  if (n_sink < 0 || n_sink > shape->n_ctx) return fail(FOCUS_EINVAL, "focus_sparse_layer: n_sink=%d not in [0, n_ctx]", n_sink);
-  if ((n_keep > 0 && !kept_blocks) || (n_sink > 0 && !sink_idx)) return fail(FOCUS_EINVAL, "focus_sparse_layer: index array is NULL");
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || (kbar && !aligned16(kbar)))
-    return fail(FOCUS_EINVAL, "focus_sparse_layer: pointers must be 16-byte aligned");
-  const SplitPlan p = plan_attention(*shape, max_active, n_keep, n_sink);
-  const LayerWs w = ws_layer(*shape, p);
-  if (!workspace || ws_bytes < w.total || !aligned16(workspace))
-    return fail(FOCUS_EWORKSPACE, "focus_sparse_layer: workspace needs %zu bytes, 16-byte aligned", w.total);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  float* part = reinterpret_cast<float*>(ws + w.sc.part);
-  float* R = scores ? scores : reinterpret_cast<float*>(ws + w.sc.scores);
-  float* part_o = reinterpret_cast<float*>(ws + w.attn + w.at.part_o);
-  float* part_ml = reinterpret_cast<float*>(ws + w.attn + w.at.part_ml);
-  hipError_t e;
-  const bool fused = n_b <= kFusedMaxBlocks && n_keep > 0;
-  if (!kbar)
-    e = launch_block_means_relevance(K, Q, focus_idx, counts, n_focus_max, *shape, nullptr, part, st);
-  else
-    e = launch_block_relevance(Q, focus_idx, counts, n_focus_max, kbar, *shape, part, st);
-  if (e != hipSuccess) return launch_fail("focus_sparse_layer(relevance)", e);
-  if (fused) {
-    FusedTopC f;
-    f.rel_part = part;
-    f.scores_out = R;
-    f.kept_out = kept_blocks;
-    f.n_focus_max = n_focus_max;
-    e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, nullptr, n_keep, sink_idx, n_sink, p, out, lse,
-                           part_o, part_ml, &f, st);
-    if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
-    return FOCUS_OK;
-  }
-  e = launch_reduce_topk(part, shape->n_heads, counts, n_focus_max, R, n_b, n_keep, kept_blocks, st);
-  if (e != hipSuccess) return launch_fail("focus_sparse_layer(top-C)", e);
-  e = launch_sparse_attn(Q, active_idx, counts, max_active, K, V, *shape, kept_blocks, n_keep, sink_idx, n_sink, p, out, lse,
-                         part_o, part_ml, nullptr, st);
-  if (e != hipSuccess) return launch_fail("focus_sparse_layer(attention)", e);
-  return FOCUS_OK;
+  return sparse_layer_impl("focus_sparse_layer", Q, focus_idx, active_idx, counts, n_focus_max, max_active, K, V, kbar, shape,
+                           n_keep, sink_idx, n_sink, scores, kept_blocks, out, lse, workspace, ws_bytes, false, stream);
+}
+
+int focus_sparse_layer_static(const void* Q, const int32_t* focus_idx, const int32_t* active_idx, const int32_t* counts,
+                              int32_t n_focus_max, int32_t max_active, const void* K, const void* V, const float* kbar,
+                              const focus_shape* shape, int32_t n_keep, const int32_t* sink_idx, int32_t n_sink,
+                              float* scores, int32_t* kept_blocks, void* out, float* lse, void* stream) {
+  return sparse_layer_impl("focus_sparse_layer_static", Q, focus_idx, active_idx, counts, n_focus_max, max_active, K, V, kbar,
+                           shape, n_keep, sink_idx, n_sink, scores, kept_blocks, out, lse, nullptr, 0, true, stream);
 }
 
 }  // extern "C"
