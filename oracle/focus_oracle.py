@@ -22,7 +22,11 @@ Readings taken where the paper leaves a choice (each restated where it is used):
     positions are sink candidates;
   * the last prompt block may be shorter than B and is averaged over its true length;
   * the key set of the sparse attention is a set: a sink inside a kept block counts once;
-  * the arg max of Eq. 2 goes to the lower token id when several tokens share the maximum.
+  * the arg max of Eq. 2 goes to the lower token id when several tokens share the maximum;
+  * Eq. 3 defines the keys a step USES: the refreshed positions enter that step's attention with their
+    newly computed states.  Alg. 1 prints the cache update after the attention and only in its dense
+    branch; here every layer (dense or sparse) first writes the new states of I_active into its cache
+    and then attends over the cache.
 
 Pins (tests/test_oracle_*.py): dense reduction against an independent attention, softmax row
 sums, brute-force top-k, closed forms (equal keys, single key, one-hot), linearity of the
@@ -39,7 +43,8 @@ import numpy as np
 __all__ = [
     "widen_bf16", "top_indices", "decision_margin", "select_focus", "expand_window", "block_means",
     "block_relevance", "select_blocks", "sink_scores", "select_sinks", "attention_index_set",
-    "sparse_attention", "focus_layer", "focus_step", "token_confidence", "cache_update",
+    "sparse_attention", "focus_layer", "focus_step", "token_confidence", "cache_update", "full_attention",
+    "decode_block",
 ]
 
 
@@ -268,3 +273,72 @@ def cache_update(K_cache, V_cache, K_new, V_new, active, row_base: int):
         K_out[:, row_base + i, :] = K_new[:, a, :]
         V_out[:, row_base + i, :] = V_new[:, a, :]
     return K_out, V_out
+
+
+# ----------------------------------------------------------------------------- Alg. 1 across a block entry
+def full_attention(Q, rows, K, V):
+    """FullAttn of Alg. 1: softmax(Q_rows K^T / sqrt(d)) V over every row of K / V, bidirectional.
+    Returns (out [H, len(rows), d], lse [H, len(rows)]) in float64."""
+    rows = np.asarray(rows, dtype=np.int64)
+    H, L, d = K.shape
+    out = np.empty((H, len(rows), d), dtype=np.float64)
+    lse = np.empty((H, len(rows)), dtype=np.float64)
+    for h in range(H):
+        logits = (_f64(Q[h])[rows] @ _f64(K[h]).T) / math.sqrt(d)
+        m = logits.max(axis=1, keepdims=True)
+        p = np.exp(logits - m)
+        z = p.sum(axis=1, keepdims=True)
+        out[h] = (p / z) @ _f64(V[h])
+        lse[h] = (m + np.log(z))[:, 0]
+    return out, lse
+
+
+def decode_block(entry, steps, n_layers: int, l_dense: int, dense_tail: int, n_ctx: int, row_base: int, block: int,
+                 window: int, lo: int, hi: int, n_keep: int, n_sink: int) -> dict:
+    """Alg. 1 for one generation block over a stack of attention layers with an approximate KV cache (Sec. 3,
+    Eq. 3): the block-entry step, then the sparse steps that follow it.
+
+    Layers are numbered from 0; layers 0 .. l_dense attend densely, layer l_dense is the one whose attention
+    identifies the sinks, the last `dense_tail` layers stay dense as well, every layer in between is sparse.
+
+    entry(l) -> (Q_all, K_all, V_all), each [H, L, d]: the states of EVERY position as computed at the block entry
+        (I_active = all positions, no pruning): the whole cache of layer l is rewritten (Eq. 3 with U = everything)
+        and every position attends to every key.
+    steps: a list, one dict per later step, with
+        'conf' [n_gen], 'masked' [n_gen] or None, 'k'  -> I_focus (Eq. 4) and I_active (Eq. 5, window / lo / hi);
+        'layer': l -> (Q [H, n_gen, d], K_new [H, >= |I_active|, d], V_new): the queries of the generation block and
+        the newly computed states of the active positions in list order.
+      In every layer the cache rows row_base + i, i in I_active, first take the new states (Eq. 3); then
+        a dense layer attends with Q[I_active] over the whole cache; at l_dense S_j (Eq. 6) is read off that
+        attention and I_sink selected; a sparse layer runs Eq. 7, Top-C, Eq. 8 and Eq. 9 on the cache with those sinks.
+    Returns {'entry': [out_l [H, L, d]], 'steps': [{'focus', 'active', 'S', 'sinks', 'layers': [..per layer dict..]}],
+             'K_cache': [..], 'V_cache': [..]} (caches after the last step).
+    """
+    K_cache, V_cache, entry_out = [], [], []
+    for l in range(n_layers):
+        Q_all, K_all, V_all = entry(l)
+        L = K_all.shape[1]
+        K_cache.append(np.array(K_all, dtype=np.float64, copy=True))
+        V_cache.append(np.array(V_all, dtype=np.float64, copy=True))
+        entry_out.append(full_attention(Q_all, np.arange(L), K_cache[l], V_cache[l])[0])
+    first_tail = n_layers - dense_tail
+    results = []
+    for st in steps:
+        focus = select_focus(st["conf"], st.get("masked"), st["k"])
+        active = expand_window(focus, window, lo, hi)
+        sinks, S, per_layer = None, None, []
+        for l in range(n_layers):
+            Q, K_new, V_new = st["layer"](l)
+            K_cache[l], V_cache[l] = cache_update(K_cache[l], V_cache[l], _f64(K_new), _f64(V_new), active, row_base)
+            if l <= l_dense or l >= first_tail:
+                out, lse = full_attention(Q, active, K_cache[l], V_cache[l])
+                rec = {"kind": "dense", "out": out, "lse": lse}
+                if l == l_dense:
+                    S = sink_scores(Q, active, K_cache[l])
+                    sinks = select_sinks(S, n_ctx, n_sink)
+            else:
+                rec = focus_layer(Q, K_cache[l], V_cache[l], focus, active, sinks, n_ctx, block, n_keep)
+                rec["kind"] = "sparse"
+            per_layer.append(rec)
+        results.append({"focus": focus, "active": active, "S": S, "sinks": sinks, "layers": per_layer})
+    return {"entry": entry_out, "steps": results, "K_cache": K_cache, "V_cache": V_cache}

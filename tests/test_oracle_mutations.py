@@ -174,3 +174,67 @@ def test_cache_update_at_the_wrong_rows_is_caught(monkeypatch):
             V_out[:, i, :] = V_new[:, a, :]
         return K_out, V_out
     assert _pins_reject(monkeypatch, "cache_update", broken, [pins.test_cache_update_touches_exactly_the_refreshed_rows])
+
+
+def _decode_block_with_a_mistake(mistake):
+    """decode_block re-stated with one planted mistake: 'update_after' (the new states reach the cache only after the
+    layer has attended), 'no_persist' (every step starts again from the block-entry cache), 'sparse_skip' (sparse layers
+    never write their new states), 'entry_prompt_only' (the block entry rewrites the prompt rows only)."""
+    def broken(entry, steps, n_layers, l_dense, dense_tail, n_ctx, row_base, block, window, lo, hi, n_keep, n_sink):
+        K0, V0, entry_out = [], [], []
+        for l in range(n_layers):
+            Q_all, K_all, V_all = entry(l)
+            K, V = np.array(K_all, dtype=np.float64), np.array(V_all, dtype=np.float64)
+            if mistake == "entry_prompt_only":
+                K[:, n_ctx:], V[:, n_ctx:] = 0.0, 0.0
+            K0.append(K)
+            V0.append(V)
+            entry_out.append(fo.full_attention(Q_all, np.arange(K.shape[1]), K, V)[0])
+        Kc, Vc = [k.copy() for k in K0], [v.copy() for v in V0]
+        out_steps = []
+        for st in steps:
+            if mistake == "no_persist":
+                Kc, Vc = [k.copy() for k in K0], [v.copy() for v in V0]
+            focus = fo.select_focus(st["conf"], st.get("masked"), st["k"])
+            active = fo.expand_window(focus, window, lo, hi)
+            sinks, S, per_layer = None, None, []
+            for l in range(n_layers):
+                Q, K_new, V_new = st["layer"](l)
+                dense = l <= l_dense or l >= n_layers - dense_tail
+                upd = lambda: fo.cache_update(Kc[l], Vc[l], _f64(K_new), _f64(V_new), active, row_base)
+                if mistake != "update_after" and not (mistake == "sparse_skip" and not dense):
+                    Kc[l], Vc[l] = upd()
+                if dense:
+                    o, lse = fo.full_attention(Q, active, Kc[l], Vc[l])
+                    rec = {"kind": "dense", "out": o, "lse": lse}
+                    if l == l_dense:
+                        S = fo.sink_scores(Q, active, Kc[l])
+                        sinks = fo.select_sinks(S, n_ctx, n_sink)
+                else:
+                    rec = fo.focus_layer(Q, Kc[l], Vc[l], focus, active, sinks, n_ctx, block, n_keep)
+                    rec["kind"] = "sparse"
+                if mistake == "update_after":
+                    Kc[l], Vc[l] = upd()
+                per_layer.append(rec)
+            out_steps.append({"focus": focus, "active": active, "S": S, "sinks": sinks, "layers": per_layer})
+        return {"entry": entry_out, "steps": out_steps, "K_cache": Kc, "V_cache": Vc}
+    return broken
+
+
+def test_the_restated_block_driver_without_a_mistake_passes_the_pins(monkeypatch):
+    # the harness itself: with no mistake planted the restatement must be accepted, or the cases below prove nothing
+    assert not _pins_reject(monkeypatch, "decode_block", _decode_block_with_a_mistake(None),
+                            [pins.test_decode_block_entry_is_dense_bidirectional_attention_of_every_position,
+                             pins.test_decode_block_step_equals_a_from_scratch_step_on_the_updated_cache,
+                             pins.test_decode_block_cache_rows_persist_and_prompt_means_stay_frozen,
+                             pins.test_decode_block_refreshed_positions_are_attended_with_their_new_states])
+
+
+@pytest.mark.parametrize("mistake,pin", [
+    ("update_after", "test_decode_block_refreshed_positions_are_attended_with_their_new_states"),
+    ("no_persist", "test_decode_block_cache_rows_persist_and_prompt_means_stay_frozen"),
+    ("sparse_skip", "test_decode_block_cache_rows_persist_and_prompt_means_stay_frozen"),
+    ("entry_prompt_only", "test_decode_block_entry_is_dense_bidirectional_attention_of_every_position"),
+])
+def test_mistakes_in_the_block_driver_are_caught(monkeypatch, mistake, pin):
+    assert _pins_reject(monkeypatch, "decode_block", _decode_block_with_a_mistake(mistake), [getattr(pins, pin)])

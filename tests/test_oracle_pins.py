@@ -404,3 +404,106 @@ def test_cache_update_touches_exactly_the_refreshed_rows():
     assert (K3 == K2).all() and (V3 == V2).all()
     K4, _ = fo.cache_update(Kc, Vc, Kn, Vn, [], base)                  # U empty: pure reuse
     assert (K4 == Kc).all()
+
+
+# ----------------------------------------------------------------------------- Alg. 1 across a block entry (decode_block)
+def test_full_attention_equals_library_attention_and_a_loop():
+    H, L, d = 2, 11, 4
+    Q, K, V = _rand(81, H, 6, d), _rand(82, H, L, d), _rand(83, H, L, d)
+    rows = [0, 2, 5]
+    out, lse = fo.full_attention(Q, rows, K, V)
+    tq, tk, tv = (torch.from_numpy(x) for x in (Q[:, rows], K, V))
+    assert np.allclose(out, torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).numpy(), atol=1e-13)
+    assert np.allclose(lse, torch.logsumexp(tq @ tk.transpose(1, 2) / math.sqrt(d), dim=-1).numpy(), atol=1e-13)
+    h, i = 1, 5                                                   # one row written out term by term
+    w = [math.exp(sum(Q[h, i, c] * K[h, j, c] for c in range(d)) / math.sqrt(d)) for j in range(L)]
+    ref = [sum(w[j] * V[h, j, c] for j in range(L)) / sum(w) for c in range(d)]
+    assert np.allclose(out[h, 2], ref, atol=1e-13)
+
+
+def _decode_case(seed=90, n_layers=5, l_dense=1, dense_tail=1, n_steps=2):
+    H, M, N, d, B, n_gen = 2, 48, 8, 8, 8, 8
+    L = M + N
+    rng = np.random.default_rng(seed)
+    ent = {l: tuple(rng.standard_normal((H, L, d)) for _ in range(3)) for l in range(n_layers)}
+    steps = []
+    masked = np.ones(n_gen, dtype=np.uint8)
+    for t in range(n_steps):
+        per_layer = {l: (rng.standard_normal((H, n_gen, d)), rng.standard_normal((H, n_gen, d)), rng.standard_normal((H, n_gen, d)))
+                     for l in range(n_layers)}
+        steps.append({"conf": rng.random(n_gen).astype(np.float32), "masked": masked.copy(), "k": 2,
+                      "layer": (lambda pl: (lambda l: pl[l]))(per_layer), "_tensors": per_layer})
+        masked[rng.integers(0, n_gen)] = 0                        # a position is unmasked between the steps
+    kw = dict(n_layers=n_layers, l_dense=l_dense, dense_tail=dense_tail, n_ctx=M, row_base=M, block=B, window=2, lo=0, hi=n_gen,
+              n_keep=2, n_sink=3)
+    return ent, steps, kw, (H, M, N, d, B, n_gen)
+
+
+def test_decode_block_entry_is_dense_bidirectional_attention_of_every_position():
+    ent, steps, kw, (H, M, N, d, B, n_gen) = _decode_case()
+    res = fo.decode_block(lambda l: ent[l], [], **kw)
+    for l in range(kw["n_layers"]):
+        tq, tk, tv = (torch.from_numpy(x) for x in ent[l])
+        assert np.allclose(res["entry"][l], torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).numpy(), atol=1e-12)
+        assert np.array_equal(res["K_cache"][l], ent[l][1]) and np.array_equal(res["V_cache"][l], ent[l][2])   # U = every position
+
+
+def test_decode_block_step_equals_a_from_scratch_step_on_the_updated_cache():
+    """The last step of a block, replayed from nothing but the caches it left behind: the one-step driver (pinned on its
+    own) on those caches must select the same sinks and blocks and give the same outputs."""
+    ent, steps, kw, (H, M, N, d, B, n_gen) = _decode_case()
+    res = fo.decode_block(lambda l: ent[l], steps, **kw)
+    last, tens = res["steps"][-1], steps[-1]["_tensors"]
+    n_layers, l_dense = kw["n_layers"], kw["l_dense"]
+    sparse = [l for l in range(n_layers) if l_dense < l < n_layers - kw["dense_tail"]]
+    assert sparse == [2, 3]
+    ref = fo.focus_step(steps[-1]["conf"], steps[-1]["masked"], 2, kw["window"], 0, n_gen,
+                        lambda l: (tens[l][0], res["K_cache"][l], res["V_cache"][l]), l_dense, sparse, M, B, kw["n_keep"], kw["n_sink"])
+    assert last["focus"].tolist() == ref["focus"].tolist() and last["active"].tolist() == ref["active"].tolist()
+    assert last["sinks"].tolist() == ref["sinks"].tolist() and np.array_equal(last["S"], ref["S"])
+    for l in sparse:
+        assert last["layers"][l]["kind"] == "sparse"
+        assert last["layers"][l]["blocks"].tolist() == ref["layers"][l]["blocks"].tolist()
+        assert np.array_equal(last["layers"][l]["out"], ref["layers"][l]["out"])
+    for l in (0, 1, 4):                                          # dense prefix, probe layer, dense tail: every key attended
+        assert last["layers"][l]["kind"] == "dense"
+        tq = torch.from_numpy(tens[l][0][:, last["active"]])
+        tk, tv = torch.from_numpy(res["K_cache"][l]), torch.from_numpy(res["V_cache"][l])
+        assert np.allclose(last["layers"][l]["out"], torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).numpy(), atol=1e-12)
+
+
+def test_decode_block_cache_rows_persist_and_prompt_means_stay_frozen():
+    ent, steps, kw, (H, M, N, d, B, n_gen) = _decode_case(seed=91, n_steps=3)
+    res = fo.decode_block(lambda l: ent[l], steps, **kw)
+    act = [r["active"].tolist() for r in res["steps"]]
+    assert any(set(act[0]) - set(act[1]) - set(act[2]))          # some position is refreshed in step 1 only
+    for l in range(kw["n_layers"]):                              # every layer, dense and sparse alike
+        for pos in range(n_gen):
+            row = M + pos
+            writers = [t for t in range(3) if pos in act[t]]
+            if not writers:                                      # never refreshed: the block-entry state (Eq. 3, reuse)
+                assert np.array_equal(res["K_cache"][l][:, row], ent[l][1][:, row])
+                assert np.array_equal(res["V_cache"][l][:, row], ent[l][2][:, row])
+            else:                                                # the state of the LAST step that refreshed it
+                t = writers[-1]
+                a = act[t].index(pos)
+                assert np.array_equal(res["K_cache"][l][:, row], steps[t]["_tensors"][l][1][:, a])
+                assert np.array_equal(res["V_cache"][l][:, row], steps[t]["_tensors"][l][2][:, a])
+        # prompt rows are never refreshed between block entries, so the representative keys formed at the entry stay valid
+        assert np.array_equal(res["K_cache"][l][:, :M], ent[l][1][:, :M])
+        assert np.array_equal(fo.block_means(res["K_cache"][l], M, B), fo.block_means(ent[l][1], M, B))
+
+
+def test_decode_block_refreshed_positions_are_attended_with_their_new_states():
+    """Eq. 3 by hand: one layer, one prompt row, one response row, zero queries and keys, so attention is the plain
+    mean of the two value rows.  The refreshed response row must enter the step with its NEW value."""
+    z = np.zeros((1, 2, 1))
+    V_all = np.array([[[1.0], [2.0]]])
+    step = {"conf": np.array([0.5], dtype=np.float32), "masked": None, "k": 1,
+            "layer": lambda l: (np.zeros((1, 1, 1)), np.zeros((1, 1, 1)), np.array([[[10.0]]]))}
+    res = fo.decode_block(lambda l: (z, z, V_all), [step], n_layers=1, l_dense=0, dense_tail=0, n_ctx=1, row_base=1, block=1,
+                          window=0, lo=0, hi=1, n_keep=1, n_sink=1)
+    assert res["entry"][0][0, :, 0].tolist() == [1.5, 1.5]
+    assert res["steps"][0]["layers"][0]["out"][0, 0, 0] == pytest.approx(5.5, abs=1e-15)     # (1 + 10) / 2, not (1 + 2) / 2
+    assert res["V_cache"][0][0, :, 0].tolist() == [1.0, 10.0]
+    assert res["steps"][0]["sinks"].tolist() == [0]
