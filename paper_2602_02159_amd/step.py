@@ -5,6 +5,9 @@ marshals every call's arguments once, and `run` enqueues the library calls in th
 prescribes, all on the current stream, with no host synchronisation between them — the index sets produced
 by one call are consumed on the device by the next.  Because a step is a fixed sequence of launches on
 fixed buffers it can also be captured into a HIP graph (`capture`) and replayed.
+
+FocusStep runs one step over layers whose K/V tensors are given; FocusDecoder owns the KV caches and sequences a
+whole generation block: the block entry, then steps with the per-layer cache updates of Eq. 3.
 """
 from __future__ import annotations
 
@@ -168,3 +171,142 @@ class FocusStep:
 
     def release_graph(self):
         self._graph = None
+
+
+class FocusDecoder:
+    """Alg. 1 of the paper for one generation block over a stack of attention layers with an approximate KV cache:
+    the block-entry step (every position recomputed, caches rewritten, block means formed) and the sparse steps after
+    it, each as a fixed sequence of C-ABI calls on fixed buffers that can be replayed as a HIP graph.
+
+    Layers are numbered from 0: layers 0 .. l_dense attend densely (l_dense is the probe layer, whose attention also
+    yields the sinks), the last `dense_tail` layers stay dense, the layers in between are sparse.  Nothing is computed
+    here; the caller (a model's projections; in the tests a random generator) fills the input buffers:
+
+      block entry   q_all[l], k_all[l], v_all[l]   bf16 [H, M+N, d]      states of every position
+      step          conf fp32 [n_gen] (or logits), masked u8 [n_gen],
+                    q[l] bf16 [H, n_gen, d], k_new[l] / v_new[l] bf16 [H, max_active, d]: slot a = position I_active[a]
+
+    run_entry():  per layer  focus_cache_refresh (cache rows <- new states, K_bar of the sparse layers from the same pass),
+                  focus_refresh_attn (every position attends to every key)            -> out_all[l]
+    run_step():   [focus_token_confidence,] focus_select_queries, then per layer focus_cache_update (Eq. 3: the active rows
+                  take their new states before the layer attends) followed by
+                    dense layer   focus_sparse_attn with every block kept
+                    probe layer   focus_probe_layer (dense attention + I_sink)
+                    sparse layer  focus_sparse_layer with the K_bar cached at the block entry -> out[l], kept[l], scores[l]
+    `row_base` is the cache row of position 0 of the generation block.
+    """
+
+    def __init__(self, n_layers: int, l_dense: int, dense_tail: int, n_heads: int, head_dim: int, n_ctx: int, n_resp: int,
+                 n_gen: int, row_base: int, block: int, k_focus: int, window: int, n_keep: int, n_sink: int, device,
+                 vocab: int | None = None):
+        assert 0 <= l_dense < n_layers and 0 <= dense_tail <= n_layers - l_dense - 1
+        self.n_layers, self.l_dense, self.first_tail = n_layers, l_dense, n_layers - dense_tail
+        H, d, L = n_heads, head_dim, n_ctx + n_resp
+        self.H, self.d, self.M, self.L, self.B, self.n_gen = H, d, n_ctx, L, block, n_gen
+        self.n_b = -(-n_ctx // block)
+        self.max_active = min(n_gen, k_focus * (2 * (window // 2) + 1))
+        dev = device
+        bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+        i32 = lambda n: torch.full((max(n, 1),), -1, dtype=torch.int32, device=dev)
+        self.k_cache = [bf(H, L, d) for _ in range(n_layers)]
+        self.v_cache = [bf(H, L, d) for _ in range(n_layers)]
+        self.kbar = [torch.zeros((H, self.n_b, d), dtype=torch.float32, device=dev) if self.is_sparse(l) else None
+                     for l in range(n_layers)]
+        self.q_all, self.k_all, self.v_all = ([bf(H, L, d) for _ in range(n_layers)] for _ in range(3))
+        self.out_all = [bf(H, L, d) for _ in range(n_layers)]
+        self.conf = torch.zeros(n_gen, dtype=torch.float32, device=dev)
+        self.masked = torch.ones(n_gen, dtype=torch.uint8, device=dev)
+        self.logits = None if vocab is None else torch.zeros((n_gen, vocab), dtype=torch.bfloat16, device=dev)
+        self.tokens = i32(n_gen)
+        self.q = [bf(H, n_gen, d) for _ in range(n_layers)]
+        self.k_new = [bf(H, self.max_active, d) for _ in range(n_layers)]
+        self.v_new = [bf(H, self.max_active, d) for _ in range(n_layers)]
+        self.out = [bf(H, self.max_active, d) for _ in range(n_layers)]
+        self.kept = [i32(n_keep) for _ in range(n_layers)]
+        self.scores = [torch.zeros(self.n_b, dtype=torch.float32, device=dev) for _ in range(n_layers)]
+        self.focus_idx, self.active_idx, self.counts, self.sink_idx = i32(k_focus), i32(self.max_active), i32(2), i32(n_sink)
+        self.col_mass = torch.zeros(L, dtype=torch.float32, device=dev)
+        self.all_blocks = torch.arange(self.n_b, dtype=torch.int32, device=dev)
+        self._keep = []
+        lib = fb.lib()
+        p = lambda t: None if t is None else C.c_void_p(t.data_ptr())
+
+        def workspace(nbytes):
+            t = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+            self._keep.append(t)
+            return t
+
+        def shape(q, k, v, out=None):
+            s = fb.make_shape(q, k, v, n_ctx, block, out)
+            self._keep.append(s)
+            return s
+
+        self.entry_calls, self.step_calls = [], []
+        for l in range(n_layers):
+            s_all = shape(self.q_all[l], self.k_cache[l], self.v_cache[l], self.out_all[l])
+            self.entry_calls.append((lib.focus_cache_refresh, (
+                p(self.k_cache[l]), p(self.v_cache[l]), C.byref(s_all), p(self.k_all[l]), p(self.v_all[l]),
+                self.k_all[l].stride(0), self.k_all[l].stride(1), p(self.kbar[l]))))
+            self.entry_calls.append((lib.focus_refresh_attn, (
+                p(self.q_all[l]), p(self.k_cache[l]), p(self.v_cache[l]), C.byref(s_all), p(self.out_all[l]), None)))
+        if self.logits is not None:
+            ws_conf = workspace(fb.token_confidence_workspace(n_gen, vocab))
+            self.step_calls.append((lib.focus_token_confidence, (
+                p(self.logits), self.logits.stride(0), p(self.masked), n_gen, vocab, p(self.tokens), p(self.conf), p(ws_conf),
+                ws_conf.numel())))
+        self.step_calls.append((lib.focus_select_queries, (
+            p(self.conf), p(self.masked), n_gen, k_focus, window, 0, n_gen, p(self.focus_idx), p(self.active_idx), self.max_active,
+            p(self.counts))))
+        for l in range(n_layers):
+            s = shape(self.q[l], self.k_cache[l], self.v_cache[l], self.out[l])
+            self.step_calls.append((lib.focus_cache_update, (
+                p(self.k_cache[l]), p(self.v_cache[l]), C.byref(s), p(self.k_new[l]), p(self.v_new[l]), self.k_new[l].stride(0),
+                self.k_new[l].stride(1), p(self.active_idx), p(self.counts), self.max_active, row_base)))
+            if l == l_dense:
+                ws = workspace(fb.workspace_bytes(fb.FN_PROBE_LAYER, s, self.max_active))
+                self.step_calls.append((lib.focus_probe_layer, (
+                    p(self.q[l]), p(self.active_idx), p(self.counts), self.max_active, p(self.k_cache[l]), p(self.v_cache[l]),
+                    C.byref(s), n_sink, p(self.out[l]), None, p(self.col_mass), p(self.sink_idx), p(ws), ws.numel())))
+            elif self.is_sparse(l):
+                ws = workspace(fb.workspace_bytes(fb.FN_SPARSE_LAYER, s, self.max_active, n_keep, n_sink))
+                self.step_calls.append((lib.focus_sparse_layer, (
+                    p(self.q[l]), p(self.focus_idx), p(self.active_idx), p(self.counts), k_focus, self.max_active,
+                    p(self.k_cache[l]), p(self.v_cache[l]), p(self.kbar[l]), C.byref(s), n_keep, p(self.sink_idx), n_sink,
+                    p(self.scores[l]), p(self.kept[l]), p(self.out[l]), None, p(ws), ws.numel())))
+            else:
+                ws = workspace(fb.workspace_bytes(fb.FN_SPARSE_ATTN, s, self.max_active, self.n_b, 0))
+                self.step_calls.append((lib.focus_sparse_attn, (
+                    p(self.q[l]), p(self.active_idx), p(self.counts), self.max_active, p(self.k_cache[l]), p(self.v_cache[l]),
+                    C.byref(s), p(self.all_blocks), self.n_b, None, 0, p(self.out[l]), None, p(ws), ws.numel())))
+        self._g_entry = self._g_step = None
+
+    def is_sparse(self, l: int) -> bool:
+        return self.l_dense < l < self.first_tail
+
+    def run_entry(self):
+        if self._g_entry is not None:
+            self._g_entry.replay()
+        else:
+            FocusStep._issue(self.entry_calls, torch.cuda.current_stream().cuda_stream)
+
+    def run_step(self):
+        if self._g_step is not None:
+            self._g_step.replay()
+        else:
+            FocusStep._issue(self.step_calls, torch.cuda.current_stream().cuda_stream)
+
+    def capture(self):
+        """Capture the block entry and the step into one HIP graph each (after one eager run of both, so that no module
+        is loaded under capture).  The eager run executes a step on whatever the input buffers hold: call this before
+        the first real block entry, or re-run the entry afterwards."""
+        self._g_entry = self._g_step = None
+        self.run_entry()
+        self.run_step()
+        torch.cuda.synchronize()
+        graphs = []
+        for calls in (self.entry_calls, self.step_calls):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                FocusStep._issue(calls, torch.cuda.current_stream().cuda_stream)
+            graphs.append(g)
+        self._g_entry, self._g_step = graphs
