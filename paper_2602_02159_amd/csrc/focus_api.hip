@@ -41,10 +41,12 @@ static void plan_queries(SplitPlan& p, int max_active) {
   p.q_pad = p.q_groups * p.q_tiles_per_group * kQTile;
 }
 
-static void plan_splits(SplitPlan& p, int n_heads, int target_groups) {
+// `round_to`: sub-tiles a workgroup consumes at a time (four wavefronts with a sub-tile each; two when the wavefronts
+// share the staged sub-tiles and the key axis advances in half rounds of two)
+static void plan_splits(SplitPlan& p, int n_heads, int target_groups, int round_to = kWavesPerGroup) {
   const int per_head = target_groups / (n_heads * p.q_groups);
   int per = ceil_div(p.n_sub, per_head > 0 ? per_head : 1);
-  per = ceil_div(per > 0 ? per : 1, kWavesPerGroup) * kWavesPerGroup;  // every wavefront gets a sub-tile
+  per = ceil_div(per > 0 ? per : 1, round_to) * round_to;
   p.per_split = per;
   p.n_split = p.n_sub > 0 ? ceil_div(p.n_sub, per) : 1;
 }
@@ -55,7 +57,7 @@ static void plan_attention_splits(SplitPlan& p, const focus_shape& s) {
   // queries): fewer, longer workgroups with pipelined key loops.  One sub-tile per wavefront (the 3 % keep
   // configurations): nothing to overlap.
   if (p.q_tiles_per_group > 1) {
-    plan_splits(p, s.n_heads, kAttnGroupsShared);
+    plan_splits(p, s.n_heads, kAttnGroupsShared, 2);
   } else if (p.per_split > kWavesPerGroup) {
     plan_splits(p, s.n_heads, kAttnGroupsPipe);
     p.pipelined = p.per_split > kWavesPerGroup;
@@ -126,21 +128,25 @@ struct SinkWs {
 // column-mass kernel re-reads.  More: the spill would outweigh K itself, so K is scanned twice — statistics first,
 // then probabilities summed over the queries on the fly — and only [q_groups * H, L] column sums are stored.
 static bool sinks_two_pass(const SplitPlan& p) { return p.q_pad > 16; }
+// the spilled logits of at most 16 queries: [H, ceil(L / 4), 16 queries, 4 keys] fp32
+static size_t spilled_logits_bytes(const focus_shape& s) {
+  const size_t L = (size_t)s.n_ctx + s.n_resp;
+  return (size_t)s.n_heads * ((L + 3) / 4) * 16 * 4 * sizeof(float);
+}
 
 static SinkWs ws_find_sinks(const focus_shape& s, const SplitPlan& p) {
   SinkWs w;
   const size_t L = (size_t)s.n_ctx + s.n_resp;
-  w.logits = 0;  // logits [H, L, 16], or column sums [q_groups * H, L]
-  size_t off = align_up(sinks_two_pass(p) ? (size_t)p.q_groups * s.n_heads * L * sizeof(float)
-                                          : (size_t)s.n_heads * L * p.q_pad * sizeof(float));
+  w.logits = 0;  // logits [H, ceil(L / 4), 16, 4], or column sums [q_groups * H, L]
+  size_t off = align_up(sinks_two_pass(p) ? (size_t)p.q_groups * s.n_heads * L * sizeof(float) : spilled_logits_bytes(s));
   w.part_ml = off;
   off += align_up((size_t)s.n_heads * p.q_pad * p.n_split * 2 * sizeof(float));
   w.lse2 = off;
   off += align_up((size_t)s.n_heads * p.q_pad * sizeof(float));
   w.col_mass = off;
   off += align_up(L * sizeof(float));
-  w.cand = off;  // first-round nominees of the sink tournament
-  off += align_up((size_t)kTournamentMaxCand * sizeof(int32_t));
+  w.cand = off;  // first-round nominees of the sink tournament: positions, then order keys
+  off += align_up((size_t)2 * kTournamentMaxCand * sizeof(int32_t));  // positions, then their keys
   w.total = off;
   return w;
 }
@@ -176,11 +182,11 @@ static ProbeWs ws_probe_layer(const focus_shape& s, const SplitPlan& pa) {
   w.lse2 = off;
   off += align_up((size_t)s.n_heads * pa.q_pad * sizeof(float));
   w.scratch = off;
-  off += align_up(sinks_two_pass(pa) ? (size_t)pa.q_groups * s.n_heads * L * sizeof(float) : (size_t)s.n_heads * L * 16 * sizeof(float));
+  off += align_up(sinks_two_pass(pa) ? (size_t)pa.q_groups * s.n_heads * L * sizeof(float) : spilled_logits_bytes(s));
   w.col_mass = off;
   off += align_up(L * sizeof(float));
   w.cand = off;
-  off += align_up((size_t)kTournamentMaxCand * sizeof(int32_t));
+  off += align_up((size_t)2 * kTournamentMaxCand * sizeof(int32_t));  // positions, then their keys
   w.total = off;
   return w;
 }
@@ -459,13 +465,12 @@ int focus_find_sinks(const void* Q, const int32_t* active_idx, const int32_t* co
   const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
   const bool prefilter = !tournament && sink_prefilter_fits(shape->n_ctx, n_sink, S);
   int32_t* cand = (tournament || prefilter) ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
-  // with two nominees per group the index list fills at most a quarter of the buffer; their keys go into its second half
-  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand / 2;
+  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand;
   e = launch_column_mass(logits, two_pass, lse2, counts, max_active, two_pass ? p.q_groups * shape->n_heads : shape->n_heads,
-                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, prefilter ? cand_keys : nullptr, st);
+                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, cand ? cand_keys : nullptr, st);
   if (e != hipSuccess) return launch_fail("focus_find_sinks(column mass)", e);
   if (tournament) {
-    e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
+    e = launch_sink_final(cand, cand_keys, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_find_sinks(top-N, tournament)", e);
   } else if (prefilter) {
     e = launch_sink_select(S, cand_keys, shape->n_ctx, n_sink, sink_idx, st);
@@ -582,13 +587,12 @@ int focus_probe_layer(const void* Q, const int32_t* active_idx, const int32_t* c
   const bool tournament = sink_tournament_fits(shape->n_ctx, n_sink);
   const bool prefilter = !tournament && sink_prefilter_fits(shape->n_ctx, n_sink, S);
   int32_t* cand = (tournament || prefilter) ? reinterpret_cast<int32_t*>(ws + w.cand) : nullptr;
-  // with two nominees per group the index list fills at most a quarter of the buffer; their keys go into its second half
-  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand / 2;
+  uint32_t* cand_keys = reinterpret_cast<uint32_t*>(ws + w.cand) + kTournamentMaxCand;
   e = launch_column_mass(scratch, two_pass, lse2, counts, max_active, two_pass ? pa.q_groups * shape->n_heads : shape->n_heads,
-                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, prefilter ? cand_keys : nullptr, st);
+                         shape->n_heads, L, S, shape->n_ctx, prefilter ? kPrefilterNominees : n_sink, cand, cand ? cand_keys : nullptr, st);
   if (e != hipSuccess) return launch_fail("focus_probe_layer(column mass)", e);
   if (tournament) {
-    e = launch_sink_final(S, cand, shape->n_ctx, n_sink, sink_idx, st);
+    e = launch_sink_final(cand, cand_keys, shape->n_ctx, n_sink, sink_idx, st);
     if (e != hipSuccess) return launch_fail("focus_probe_layer(top-N, tournament)", e);
   } else if (prefilter) {
     e = launch_sink_select(S, cand_keys, shape->n_ctx, n_sink, sink_idx, st);

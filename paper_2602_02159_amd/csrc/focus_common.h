@@ -57,6 +57,16 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
   return v;
 }
 
+// sum of x over the 16 lanes of a DPP row (the lanes that hold the 16 queries of a tile for the same keys); every
+// lane of the row receives the total
+__device__ __forceinline__ float row_sum16(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, false));  // row_half_mirror
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, false));  // row_mirror
+  return x;
+}
+
 // Workgroup exclusive scan of one uint32 per thread.  `wsum` is shared memory of at least
 // blockDim/64 + 1 words.  Returns the exclusive prefix; *total gets the sum over the workgroup.
 // Contains two barriers: every thread of the workgroup must call it.

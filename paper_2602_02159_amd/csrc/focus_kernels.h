@@ -56,8 +56,8 @@ constexpr int kTournamentMaxSinks = 16;
 constexpr int kTournamentMaxCand = 4096;  // ceil(M / 128) * n_sink
 bool sink_tournament_fits(int M, int n_sink);
 // cand: nullptr, or int32[ceil(M / 128) * n_sink] that receives the nominees (requires sink_tournament_fits);
-// cand_keys: nullptr, or uint32 of the same size that receives their order keys + 1 (0 where cand holds -1).
-// pre_reduced = false: src = scaled logits [H, L, 16] of at most 16 queries, n_parts = H;
+// cand_keys: uint32 of the same size that receives their order keys + 1 (0 where cand holds -1); required with cand.
+// pre_reduced = false: src = scaled logits [H, ceil(L / 4), 16, 4] of at most 16 queries (written by the MFMA kernels), n_parts = H;
 // pre_reduced = true:  src = column sums [n_parts, L] from the second pass over K.
 hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
                               int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, uint32_t* cand_keys,
@@ -68,7 +68,7 @@ constexpr int kPrefilterNominees = 2;
 bool sink_prefilter_fits(int M, int n_sink, const float* col_mass);
 hipError_t launch_sink_select(const float* col_mass, const uint32_t* cand_keys, int M, int n_sink, int32_t* sink_idx,
                               hipStream_t st);
-hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
+hipError_t launch_sink_final(const int32_t* cand, const uint32_t* cand_keys, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st);
 
 // Eq. 2: tokens[i] = argmax over the vocabulary of row i of the bf16 logits, conf[i] = its softmax probability
@@ -85,7 +85,7 @@ hipError_t launch_cache_refresh(void* K_cache, void* V_cache, const focus_shape&
                                 int64_t new_stride_h, int64_t new_stride_n, float* kbar, hipStream_t st);
 
 // ---- MFMA kernels (focus_mfma.hip)
-// mode 0: logits [H, L, q_pad] + part_ml out; mode 1: part_ml out only; mode 2: lse2 in, colpart [q_groups * H, L] out
+// mode 0: logits [H, ceil(L / 4), 16, 4] + part_ml out (at most 16 queries); mode 1: part_ml out only; mode 2: lse2 in, colpart [q_groups * H, L] out
 hipError_t launch_qk_logits(const void* Q, const int32_t* active_idx, const int32_t* counts, int max_active,
                             const void* K, const focus_shape& s, const SplitPlan& p, int mode, float* logits,
                             float* part_ml, const float* lse2, float* colpart, hipStream_t st);

@@ -349,6 +349,23 @@ __device__ __forceinline__ bf16x8 read_v_operand(const char* stageV, int ct, int
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// Scaled logits of one 32-key sub-tile (contiguous rows row0 .., row0 a multiple of 32) against up to 16 queries, kept
+// for the column-mass kernel in the layout [head][key quad][query][key within the quad] (fp32): a lane holds, per
+// 16-key tile, the logits of ONE query for four consecutive keys — one 16-byte store — and the 64 lanes of a store
+// instruction cover 1 KB of consecutive bytes (query fastest, then the four quads of the tile).  Quads that start at or
+// past key L are not written; the padding keys of the last quad hold finite values nobody reads.
+__device__ __forceinline__ void spill_logits(float* __restrict__ logits, int h, int L, int row0, const floatx4 (&acc)[2],
+                                             float scale_log2, int lane) {
+  const int c = lane & 15, g = lane >> 4;
+  const int64_t n_quads = (L + 3) >> 2;
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    const int key0 = row0 + 16 * kt + 4 * g;
+    if (key0 < L)
+      *reinterpret_cast<floatx4*>(logits + (((int64_t)h * n_quads + (key0 >> 2)) * 16 + c) * 4) = acc[kt] * scale_log2;
+  }
+}
+
 // One step of the base-2 online softmax for the 8 logits a lane holds of one query; returns the rescale factor
 // of the running state and leaves exp2(scale * s - m) in ps.  The running maximum m is kept in the scaled domain;
 // the scale (> 0) is applied to the raw maximum once and folded into the exponent's multiply-add for the rest.
@@ -414,20 +431,19 @@ struct AttnArgs {
   // dense (probe) layer only
   int groups_first;   // grid x = query group, z = key split (see the kernel)
   int dense_rows;     // > 0: attend to all of the first dense_rows = M + N key rows, block and sink lists unused
-  float* logits_out;  // [H, L, 16] scaled base-2 logits of the (at most 16) active queries, or null
+  float* logits_out;  // [H, ceil(L / 4), 16, 4] scaled base-2 logits of the (at most 16) active queries (spill_logits), or null
   float* lse2_out;    // [H, q_pad] base-2 log-sum-exp per row (+inf for an empty row), or null
 };
 
 // Merge of per-split partial results for one (head, active row a): out = sum_s f_s O_s / sum_s f_s l_s with
 // f_s = exp2(m_s - running max), splits taken in index order, eight loads in flight at a time.  Thread = D/16 columns.
-template <int D>
+template <int D, int kBatch>
 __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, const float* __restrict__ part_ml, int h, int a,
-                                             int mc, int q_pad, int n_split, int max_active, uint16_t* __restrict__ out,
+                                             int mc, int q_pad, int n_split, int max_active, int n_act, uint16_t* __restrict__ out,
                                              int64_t osh, int64_t osn, float* __restrict__ lse, float* __restrict__ lse2,
                                              bool write_lse) {
   constexpr int kPerThread = D / 16;
   constexpr int kVec = kPerThread / 4;
-  constexpr int kBatch = 8;
   const int64_t row0 = ((int64_t)h * q_pad + a) * n_split;
   const float2* ml = reinterpret_cast<const float2*>(part_ml) + row0;
   const float* po = part_o + row0 * D + mc;
@@ -463,6 +479,7 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
       }
     }
   }
+  if (a >= n_act) return;  // rows past the device-side count: their partial results were never written and are not used
   const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
   uint16_t* dst = out + (int64_t)h * osh + (int64_t)a * osn + mc;
 #pragma unroll
@@ -654,14 +671,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) {  // one staged sub-tile into the running softmax
     floatx4 acc[1][2];
     qk_subtile<D, 1>(acc, sK, q, lane);
-    if (SPILL) {  // contiguous rows only (dense): key row = row0 + slot
-      float* dst = p.logits_out + ((int64_t)h * p.dense_rows + row0) * 16 + c;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-        if ((vmask >> slot) & 1u) dst[slot * 16] = acc[0][e >> 2][e & 3] * p.scale_log2;
-      }
-    }
+    if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, row0, acc[0], p.scale_log2, lane);  // contiguous rows only (dense)
     float ps[8];
     const float alpha = softmax_step(acc[0], vmask, g, p.scale_log2, m_run, l_run, ps);
     // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
@@ -832,8 +842,9 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
 
 // Merge of the per-split partial results: out = sum_s f_s O_s / sum_s f_s l_s, f_s = exp2(m_s - max m).
 // One workgroup per (head, 16 queries); thread = (query, D/16 columns).  Fixed order over splits; the loads of
-// eight splits are issued together so the kernel is a few memory round trips long whatever the split count.
-template <int D>
+// kBatch splits are issued together — and together with the load of the device-side query count, which is only looked
+// at when the row is stored — so the kernel is one memory round trip long for up to kBatch splits.
+template <int D, int kBatch>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_ml,
                                                            const int32_t* __restrict__ counts, int max_active, int q_pad,
@@ -842,9 +853,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
   const int h = blockIdx.y;
   const int a = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int mc = (threadIdx.x & 15) * (D / 16);
+  if (a >= max_active) return;  // host-side capacity of the active list; rows below it exist in the workspace
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  if (a >= n_act) return;
-  merge_splits<D>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, out, osh, osn, lse, lse2, (threadIdx.x & 15) == 0);
+  merge_splits<D, kBatch>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, n_act, out, osh, osn, lse, lse2,
+                          (threadIdx.x & 15) == 0);
 }
 
 template <int D, int QT>
@@ -868,8 +880,12 @@ static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fuse
     hipLaunchKernelGGL((sparse_attn_kernel<D, QT, 0>), grid, block, 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
-  hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
-                     a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
+  if (p.n_split <= 8)
+    hipLaunchKernelGGL((attn_combine_kernel<D, 8>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
+                       a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
+  else
+    hipLaunchKernelGGL((attn_combine_kernel<D, 16>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
+                       a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
   return hipGetLastError();
 }
 
@@ -1295,7 +1311,7 @@ struct LogitArgs {
   const uint16_t* K;
   const int32_t* active_idx;
   const int32_t* counts;
-  float* logits;      // [H, L, q_pad]                         (mode 0)
+  float* logits;      // [H, ceil(L / 4), 16, 4]: see spill_logits  (mode 0, at most 16 queries)
   float* part_ml;     // [H, q_pad, n_split, 2]                (modes 0, 1)
   const float* lse2;  // [H, q_pad] base-2 log-sum-exp per row (mode 2)
   float* colpart;     // [q_groups * H, L]                     (mode 2)
@@ -1304,16 +1320,6 @@ struct LogitArgs {
   int n_sub, per_split, n_split, q_pad;
   float scale_log2;
 };
-
-// sum of x over the 16 lanes of a DPP row (the lanes that hold the 16 queries of a tile for the same keys); every
-// lane of the row receives the total
-__device__ __forceinline__ float row_sum16(float x) {
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, false));  // row_half_mirror
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, false));  // row_mirror
-  return x;
-}
 
 // MODE 0: the scaled logits are written out (for up to 16 queries re-reading 64 bytes per key and head is cheaper
 //         than a second pass over K) together with the per-split softmax statistics.
@@ -1409,14 +1415,7 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
       for (int qt = 0; qt < NQT; ++qt) {
         float ps[8];
         softmax_step(acc[qt], cur.vmask, g, p.scale_log2, m_run[qt], l_run[qt], ps);
-        if (MODE == 0) {
-          float* dst = p.logits + ((int64_t)h * p.L + cur.row0) * p.q_pad + q_base + qt * kQTile + c;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int slot = 16 * (e >> 2) + 4 * g + (e & 3);
-            if ((cur.vmask >> slot) & 1u) dst[(int64_t)slot * p.q_pad] = acc[qt][e >> 2][e & 3] * p.scale_log2;
-          }
-        }
+        if (MODE == 0) spill_logits(p.logits, h, p.L, cur.row0, acc[qt], p.scale_log2, lane);  // one query tile (NQT == 1)
       }
     }
   }

@@ -419,17 +419,20 @@ hipError_t launch_lse_combine(const float* part_ml, int H, int q_pad, int n_spli
   return hipGetLastError();
 }
 
-// Column attention mass S_j (Eq. 6) from what the first stage left behind.  Workgroup = 128 keys x 4 part groups
-// (512 threads); thread (key, pg) walks parts pg, pg + 4, ...
-//   PRE = false: `src` holds the scaled logits [H, L, 16] fp32 of at most 16 active queries and lse2 their row
-//                log-sum-exps [H, 16]; a part is a head, its contribution sum_i exp2(logit - lse).  The loads of four
-//                heads (16 x 16 bytes) are issued before the first exp2.
-//   PRE = true:  `src` holds per-part column sums [n_parts, L] (already summed over a part's queries); they are
-//                added up, eight loads in flight.
+// Column attention mass S_j (Eq. 6) from what the first stage left behind.  Workgroup = 128 keys, 512 threads.
+//   PRE = false: `src` holds the scaled logits of at most 16 active queries in the layout
+//                [head][key quad][query][key within the quad] (fp32) and lse2 their row log-sum-exps [H, 16].  Lane
+//                (query c, quad qd) of wavefront w owns the four keys of quad 4 w + qd for query c: one 16-byte load
+//                per head, the 64 lanes of a load instruction reading 1 KB of consecutive bytes; sixteen heads are in
+//                flight at a time.  It adds exp2(logit - lse) over the heads in head order; the sixteen queries of a
+//                quad are then summed across the lanes of a DPP row (fixed tree).
+//   PRE = true:  `src` holds per-part column sums [n_parts, L] (already summed over a part's queries); thread
+//                (key, part group pg) adds parts pg, pg + 4, ..., eight loads in flight, then the four groups are added.
 // S_j = total / (H * n_act).
 // With cand != nullptr (small N_sink) the workgroup also plays the first round of the sink tournament: the n_sink
 // largest masses among its own prompt positions (j < M; ties to the lower j) go to cand[wg * n_sink ..], ascending,
-// padded with -1.  The overall Top-N_sink is a subset of the union of these lists (sink_final_kernel).
+// padded with -1, and their order keys + 1 to cand_keys at the same places (0 beside a -1).  The overall Top-N_sink is
+// a subset of the union of these lists (sink_final_kernel).
 constexpr int kMassKeys = 128;
 
 template <bool PRE>
@@ -438,14 +441,16 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
                                                           int H, int L, float* __restrict__ col_mass, int M, int n_sink,
                                                           int32_t* __restrict__ cand, uint32_t* __restrict__ cand_keys) {
   __shared__ float red[4][kMassKeys];
+  __shared__ float mass_sh[kMassKeys];
   __shared__ __attribute__((aligned(16))) uint32_t ckeys[256];
   __shared__ uint32_t ctotal;
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  const int kj = threadIdx.x & (kMassKeys - 1), pg = threadIdx.x / kMassKeys;
-  const int j = blockIdx.x * kMassKeys + kj;
-  float acc = 0.f;
-  if (j < L) {
-    if (PRE) {
+  const float norm = n_act > 0 ? 1.f / ((float)H * (float)n_act) : 0.f;
+  if (PRE) {
+    const int kj = threadIdx.x & (kMassKeys - 1), pg = threadIdx.x / kMassKeys;
+    const int j = blockIdx.x * kMassKeys + kj;
+    float acc = 0.f;
+    if (j < L) {
       for (int q0 = pg; q0 < n_parts; q0 += 32) {
         float x[8];
 #pragma unroll
@@ -456,47 +461,56 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += x[u];
       }
-    } else {
-      for (int h0 = pg; h0 < n_parts; h0 += 16) {
-        float4 x[4][4];
+    }
+    red[pg][kj] = acc;
+    __syncthreads();
+    if (pg == 0) mass_sh[kj] = ((red[0][kj] + red[1][kj]) + (red[2][kj] + red[3][kj])) * norm;
+  } else {
+    constexpr int kHeadsInFlight = 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, qd = lane >> 4;
+    const int quad_local = wave * 4 + qd;                                    // 0 .. 31
+    const int64_t n_quads = (L + 3) >> 2;
+    const int64_t quad = (int64_t)blockIdx.x * (kMassKeys / 4) + quad_local;  // key quad of this lane
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (quad < n_quads) {
+      const float4* base = reinterpret_cast<const float4*>(src) + quad * 16 + c;
+      for (int h0 = 0; h0 < n_parts; h0 += kHeadsInFlight) {
+        float4 x[kHeadsInFlight];
+        float z[kHeadsInFlight];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int h = h0 + 4 * u;
-          const float4* lp = reinterpret_cast<const float4*>(src + ((int64_t)(h < n_parts ? h : pg) * L + j) * 16);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) x[u][i] = lp[i];
+        for (int u = 0; u < kHeadsInFlight; ++u) {
+          const int h = min(h0 + u, n_parts - 1);  // clamped: stays in bounds, ignored below
+          x[u] = base[(int64_t)h * n_quads * 16];
+          z[u] = lse2[(int64_t)h * 16 + c];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int h = h0 + 4 * u;
-          if (h < n_parts) {
-            const float4* ls = reinterpret_cast<const float4*>(lse2 + (int64_t)h * 16);
-            float a = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const float4 z = ls[i];
-              const int i0 = 4 * i;
-              if (i0 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].x - z.x);
-              if (i0 + 1 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].y - z.y);
-              if (i0 + 2 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].z - z.z);
-              if (i0 + 3 < n_act) a += __builtin_amdgcn_exp2f(x[u][i].w - z.w);
-            }
-            acc += a;
+        for (int u = 0; u < kHeadsInFlight; ++u) {
+          if (h0 + u < n_parts) {
+            acc[0] += __builtin_amdgcn_exp2f(x[u].x - z[u]);
+            acc[1] += __builtin_amdgcn_exp2f(x[u].y - z[u]);
+            acc[2] += __builtin_amdgcn_exp2f(x[u].z - z[u]);
+            acc[3] += __builtin_amdgcn_exp2f(x[u].w - z[u]);
           }
         }
       }
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = row_sum16(c < n_act ? acc[r] : 0.f);  // query slots past the count add nothing
+    if (c == 0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) mass_sh[quad_local * 4 + r] = acc[r] * norm;
+    }
   }
-  red[pg][kj] = acc;
   __syncthreads();
   float mass = 0.f;
-  if (pg == 0 && j < L) {
-    const float tot = (red[0][kj] + red[1][kj]) + (red[2][kj] + red[3][kj]);
-    mass = n_act > 0 ? tot / ((float)H * (float)n_act) : 0.f;
+  const int j = blockIdx.x * kMassKeys + threadIdx.x;  // threads 0 .. 127: one key each
+  if (threadIdx.x < kMassKeys && j < L) {
+    mass = mass_sh[threadIdx.x];
     col_mass[j] = mass;
   }
   if (cand != nullptr && blockIdx.x * kMassKeys < M) {  // uniform over the workgroup
-    if (threadIdx.x < 256) ckeys[threadIdx.x] = (pg == 0 && j < M) ? order_key(mass) + 1u : 0u;
+    if (threadIdx.x < 256) ckeys[threadIdx.x] = (threadIdx.x < kMassKeys && j < M) ? order_key(mass) + 1u : 0u;
     __syncthreads();
     if (threadIdx.x < kWave)
       wave_topk<4>(ckeys, 256, n_sink, cand + (int64_t)blockIdx.x * n_sink, nullptr, &ctotal, blockIdx.x * kMassKeys, nullptr,
@@ -505,11 +519,11 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
 }
 
 // Final rounds of the sink tournament over the n_cand = n_groups * n_sink first-round winners (n_sink <= 16,
-// n_cand <= 4096; cand ascending in j apart from -1 padding).  Round two: wavefront w ranks candidates
+// n_cand <= 4096; cand ascending in j apart from -1 padding, cand_keys their order keys + 1, 0 beside a -1).  Round two: wavefront w ranks candidates
 // [256 w, 256 w + 256); round three: one wavefront ranks the <= 256 survivors.  Every round keeps the order
 // (value descending, index ascending) and lists its winners by ascending position, so the result is the exact Top-N_sink
 // in ascending order.
-__global__ __launch_bounds__(1024) void sink_final_kernel(const float* __restrict__ col_mass, const int32_t* __restrict__ cand,
+__global__ __launch_bounds__(1024) void sink_final_kernel(const int32_t* __restrict__ cand, const uint32_t* __restrict__ cand_keys,
                                                          int n_cand, int n_sink, int32_t* __restrict__ sink_idx) {
   __shared__ __attribute__((aligned(16))) uint32_t keys1[16][256];
   __shared__ __attribute__((aligned(16))) uint32_t keys2[256];
@@ -517,14 +531,11 @@ __global__ __launch_bounds__(1024) void sink_final_kernel(const float* __restric
   __shared__ int32_t win2[16];
   __shared__ uint32_t tot1[16], tot2;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  int32_t cj[4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
+  for (int r = 0; r < 4; ++r) {  // the nominees' keys were written beside their positions: no trip to the column masses
     const int ci = w * 256 + lane * 4 + r;
-    cj[r] = ci < n_cand ? cand[ci] : -1;
+    keys1[w][lane * 4 + r] = ci < n_cand ? cand_keys[ci] : 0u;
   }
-#pragma unroll
-  for (int r = 0; r < 4; ++r) keys1[w][lane * 4 + r] = cj[r] >= 0 ? order_key(col_mass[cj[r]]) + 1u : 0u;
   __syncthreads();
   if (w * 256 < n_cand) wave_topk<4>(keys1[w], 256, n_sink, win1[w], nullptr, &tot1[w]);  // blockDim covers these waves
   __syncthreads();
@@ -546,11 +557,12 @@ bool sink_tournament_fits(int M, int n_sink) {
   return n_sink >= 1 && n_sink <= kTournamentMaxSinks && (int64_t)ceil_div(M, kMassKeys) * n_sink <= kTournamentMaxCand;
 }
 
-// pre_reduced = false: src = logits [H, L, 16], n_parts = H.  pre_reduced = true: src = column sums [n_parts, L].
+// pre_reduced = false: src = logits [H, ceil(L / 4), 16, 4], n_parts = H.  pre_reduced = true: src = column sums [n_parts, L].
 hipError_t launch_column_mass(const float* src, bool pre_reduced, const float* lse2, const int32_t* counts, int max_active,
                               int n_parts, int H, int L, float* col_mass, int M, int n_sink, int32_t* cand, uint32_t* cand_keys,
                               hipStream_t st) {
   if (cand != nullptr && !sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;  // n_sink: nominees per group
+  if (!pre_reduced && n_parts < 1) return hipErrorInvalidValue;
   if (pre_reduced)
     hipLaunchKernelGGL(column_mass_kernel<true>, dim3(ceil_div(L, kMassKeys)), dim3(512), 0, st, src, lse2, counts,
                        max_active, n_parts, H, L, col_mass, M, n_sink, cand, cand_keys);
@@ -691,12 +703,12 @@ hipError_t launch_sink_select(const float* col_mass, const uint32_t* cand_keys, 
   return hipGetLastError();
 }
 
-hipError_t launch_sink_final(const float* col_mass, const int32_t* cand, int M, int n_sink, int32_t* sink_idx,
+hipError_t launch_sink_final(const int32_t* cand, const uint32_t* cand_keys, int M, int n_sink, int32_t* sink_idx,
                              hipStream_t st) {
   if (!sink_tournament_fits(M, n_sink)) return hipErrorInvalidValue;
   const int n_cand = ceil_div(M, kMassKeys) * n_sink;
   const int threads = std::max(256, ceil_div(n_cand, 256) * 64);  // one wavefront per 256 nominees, at least the 256 of round three
-  hipLaunchKernelGGL(sink_final_kernel, dim3(1), dim3(threads), 0, st, col_mass, cand, n_cand, n_sink, sink_idx);
+  hipLaunchKernelGGL(sink_final_kernel, dim3(1), dim3(threads), 0, st, cand, cand_keys, n_cand, n_sink, sink_idx);
   return hipGetLastError();
 }
 
