@@ -205,6 +205,27 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
   }
 }
 
+// The loads [first, first + NL) of a sub-tile only, straight into LDS (a wavefront's share when several wavefronts
+// stage one sub-tile).  Same layout as issue_subtile.
+template <int D, int NL>
+__device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
+                                                   const int32_t* __restrict__ sink_idx, int n_sink, char* stage, int lane,
+                                                   int first) {
+  using G = Geo<D>;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
+  const int last = 31 - __builtin_clz(t.vmask);
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int slot = (first + i) * G::kRowsPerLoad + sub;
+    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
+    const int chunk = pos ^ (slot & (G::kChunks - 1));
+    const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + (first + i) * 1024), 16, 0, kStreamPolicy);
+  }
+}
+
 // The same sub-tile through registers, for the double-buffered key loops: fetch_subtile requests the rows (the
 // loads stay in flight while the previous sub-tile is multiplied), store_subtile puts them into a stage in exactly
 // the layout issue_subtile produces.  (LDS-direct loads cannot be overlapped with LDS reads of another stage: the
@@ -224,27 +245,6 @@ __device__ __forceinline__ void fetch_subtile(const uint16_t* __restrict__ base,
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
   }
-}
-// The loads [first, first + NL) of a sub-tile only (a wavefront's share when several wavefronts stage one sub-tile).
-template <int D, int NL>
-__device__ __forceinline__ void fetch_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
-                                                   const int32_t* __restrict__ sink_idx, int n_sink, int lane, int first,
-                                                   uintx4 (&r)[NL]) {
-  using G = Geo<D>;
-  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
-  const int last = 31 - __builtin_clz(t.vmask);
-#pragma unroll
-  for (int i = 0; i < NL; ++i) {
-    const int slot = (first + i) * G::kRowsPerLoad + sub;
-    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
-    const int chunk = pos ^ (slot & (G::kChunks - 1));
-    r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
-  }
-}
-template <int D, int NL>
-__device__ __forceinline__ void store_subtile_part(char* stage, int lane, int first, const uintx4 (&r)[NL]) {
-#pragma unroll
-  for (int i = 0; i < NL; ++i) *reinterpret_cast<uintx4*>(stage + (first + i) * 1024 + lane * 16) = r[i];
 }
 template <int D>
 __device__ __forceinline__ void store_subtile(char* stage, int lane, const uintx4 (&r)[Geo<D>::kLoads]) {
@@ -498,12 +498,12 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
 //   at the end.
 // QT = 2 / 4 (17..32 / 33..64 active queries per group), four / eight wavefronts: the staged sub-tiles are shared and
 //   the key axis advances in half rounds of two sub-tiles.  Wavefront w works for query tile w % QT on member
-//   w / QT of the half round's slot pair; meanwhile the rows of the next two sub-tiles travel into registers (each
-//   wavefront fetches its share: one K or V tile with four wavefronts, half of one with eight) and are stored into
-//   the other slot pair once the previous half round has released it.  Every K/V byte is still fetched once per
-//   workgroup, every wavefront carries the accumulators of ONE query tile, and two workgroups per compute unit put
-//   2 (QT = 2) or 4 (QT = 4) wavefronts on each SIMD: a lone wavefront cannot hide the LDS and MFMA latencies of its
-//   own chain (measured: ~1 us per sub-tile and query tile, four times the arithmetic).
+//   w / QT of the half round's pair; meanwhile the rows of the next two sub-tiles travel from HBM straight into the
+//   other LDS buffer (each wavefront requests its share: one K or V tile with four wavefronts, half of one with eight;
+//   LDS-direct loads, no staging registers, no LDS stores).  Every K/V byte is fetched once per workgroup, every
+//   wavefront carries the accumulators of ONE query tile, and two workgroups per compute unit put 2 (QT = 2) or 4
+//   (QT = 4) wavefronts on each SIMD: a lone wavefront cannot hide the LDS and MFMA latencies of its own chain
+//   (measured: ~1 us per sub-tile and query tile, four times the arithmetic).
 //
 // FUSE bit 0 clear: kept_blocks comes from memory.
 // FUSE bit 0 set (fused layer path): the workgroup first assembles R_b from the per-head partial relevances and ranks
@@ -532,10 +532,12 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   constexpr int kBufBytes = 2 * G::kStageBytes;          // one slot: K stage + V stage of a sub-tile
   constexpr int kMergeBytes = 16 * D * 4;                // one wavefront's O tile in the final merge
   static_assert(QT == 1 || QT == 2 || QT == 4, "query tiles per workgroup");
-  static_assert(W * kMergeBytes <= kWavesPerGroup * kBufBytes, "merge scratch fits the stages");
   // Two buffers of four slots; the second exists in the double-buffered variant only.
-  __shared__ __attribute__((aligned(16))) char ldsA[kWavesPerGroup * kBufBytes];
-  __shared__ __attribute__((aligned(16))) char ldsB[PIPE ? kWavesPerGroup * kBufBytes : 16];
+  // (SHARED: buffer A holds the two slots of the even half rounds, buffer B those of the odd ones — two separate arrays,
+  // so that the compiler can tell an LDS-direct load into one from the operand reads of the other.)
+  __shared__ __attribute__((aligned(16))) char ldsA[(SHARED ? 2 : kWavesPerGroup) * kBufBytes];
+  __shared__ __attribute__((aligned(16))) char ldsB[PIPE ? kWavesPerGroup * kBufBytes : (SHARED ? 2 * kBufBytes : 16)];
+  static_assert(!SHARED || 4 * kMergeBytes <= 2 * kBufBytes, "merge scratch of four wavefronts fits one buffer");
   __shared__ uint32_t maskA[kWavesPerGroup];  // SHARED: the keys of each slot that take part
   __shared__ float2 ml_sh[W][16];             // final merge: running maximum and sum per wavefront and query
 
@@ -622,8 +624,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   // SHARED: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
   // the half round's sub-tile (w & 1)
   const int h_i = wave & 1, h_kv = (wave >> 1) & 1, h_first = (wave >> 2) * NLH;
-  uintx4 rh[NLH];
-  auto fetch_half = [&](int ph) {  // request this wavefront's share of half round ph; returns its sub-tile
+  // SHARED: this wavefront's share of half round ph goes straight into buffer `buf` (A for even ph, B for odd ph)
+  auto dma_half = [&](int ph, char* buf) __attribute__((always_inline)) {
     SubTile tp;
     tp.kind = 0;
     tp.row0 = 0;
@@ -633,17 +635,11 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows);
     if (tp.vmask != 0u)
-      fetch_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink, lane, h_first, rh);
-    return tp;
+      issue_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink,
+                                 buf + h_i * kBufBytes + h_kv * G::kStageBytes, lane, h_first);
+    if (h_kv == 0 && h_first == 0 && lane == 0) maskA[2 * (ph & 1) + h_i] = tp.vmask;
   };
-  auto store_half = [&](int ph, const SubTile& tp) {  // ... and put it into its slot once the slot is free
-    const int sl = (2 * ph + h_i) & (kWavesPerGroup - 1);
-    if (tp.vmask != 0u)
-      store_subtile_part<D, NLH>(ldsA + sl * kBufBytes + h_kv * G::kStageBytes, lane, h_first, rh);
-    if (h_kv == 0 && h_first == 0 && lane == 0) maskA[sl] = tp.vmask;
-  };
-  SubTile t_half;
-  if (SHARED) t_half = fetch_half(0);
+  if (SHARED) dma_half(0, ldsA);
   if (!SHARED && st < st_end) {
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows);
@@ -668,7 +664,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   bool first = true;
-  auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) {  // one staged sub-tile into the running softmax
+  auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) __attribute__((always_inline)) {  // one staged sub-tile into the running softmax
     floatx4 acc[1][2];
     qk_subtile<D, 1>(acc, sK, q, lane);
     if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, row0, acc[0], p.scale_log2, lane);  // contiguous rows only (dense)
@@ -704,27 +700,32 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     store_subtile<D>(stageV, lane, rv);
   }
   if (SHARED) {
-    // Half rounds: while two slots are multiplied (wavefront w: slot pair's member w / 4, for query tile w % 4), the
-    // rows of the next two sub-tiles are on their way into registers; they are stored into the other two slots, which
-    // the previous half round has finished with, before the barrier that opens the next half round.  Loads are in
-    // flight all the time: a request is issued as soon as the registers of the previous one have been stored.
-    store_half(0, t_half);
+    // Half rounds of two sub-tiles (wavefront w multiplies member w / QT of the pair for query tile w % QT).  While half
+    // round ph is multiplied out of one buffer, the rows of half round ph + 1 travel from HBM straight into the other —
+    // for the whole of that time, with no staging registers and no LDS stores.  A wavefront's loads have landed when
+    // its vmcnt reaches zero; the barrier then tells everyone that all shares have landed and that the buffer just read
+    // is free.  Unrolled by two, so that every access names its buffer statically: the compiler then knows that an
+    // LDS-direct load into one buffer does not touch the operand reads of the other and does not wait for it.
     const int n_half = (st_end - st_begin + 1) / 2;  // uniform over the workgroup
-    SubTile tn = no_tile();
-    if (1 < n_half) tn = fetch_half(1);
-    for (int ph = 0; ph < n_half; ++ph) {
-      __syncthreads();  // half round ph is staged; everyone is done with half round ph - 1
-      const int sl = (2 * ph + kg) & (kWavesPerGroup - 1);
-      const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[sl]);
+    auto consume_buf = [&](int ph, const char* buf) __attribute__((always_inline)) {
+      const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[2 * (ph & 1) + kg]);
       if (vm != 0u) {
-        const char* cK = ldsA + sl * kBufBytes;
+        const char* cK = buf + kg * kBufBytes;
         consume(cK, cK + G::kStageBytes, vm, 0);
       }
-      if (ph + 1 < n_half) {  // the rows requested a whole half round ago go into the slots freed by half round ph - 1,
-        store_half(ph + 1, tn);  // and the registers take the request after next straight away
-        tn = no_tile();
-        if (ph + 2 < n_half) tn = fetch_half(ph + 2);
-      }
+    };
+    wait_loads();
+    __syncthreads();  // half round 0 is staged
+    for (int ph = 0; ph < n_half; ph += 2) {
+      if (ph + 1 < n_half) dma_half(ph + 1, ldsB);  // buffer B was last read in half round ph - 1, before the last barrier
+      consume_buf(ph, ldsA);
+      wait_loads();
+      __syncthreads();  // half round ph + 1 is staged; everyone is done with buffer A
+      if (ph + 1 >= n_half) break;  // uniform
+      if (ph + 2 < n_half) dma_half(ph + 2, ldsA);
+      consume_buf(ph + 1, ldsB);
+      wait_loads();
+      __syncthreads();
     }
   } else if (!PIPE) {
     while (st < st_end) {
@@ -771,7 +772,11 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   }
 
   // ---- merge the wavefronts that share a query tile through LDS (the stages are free by now)
-  float* myO = reinterpret_cast<float*>(ldsA + wave * kMergeBytes);  // [16][D]
+  // scratch of wavefront w: its O tile, in the stage buffers (SHARED: four wavefronts per buffer)
+  auto merge_tile = [&](int w) __attribute__((always_inline)) -> char* {
+    return SHARED ? ((w < 4 ? ldsA : ldsB) + (w & 3) * kMergeBytes) : (ldsA + w * kMergeBytes);
+  };
+  float* myO = reinterpret_cast<float*>(merge_tile(wave));  // [16][D]
   constexpr int kPerThread = D / 16;                                  // output columns per thread in the merge
   constexpr int kVec = kPerThread / 4;
   constexpr int kTilesPerPass = W / kWavesPerGroup;                   // 256 threads merge one query tile
@@ -794,7 +799,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       ml[k] = ml_sh[w][mq];
 #pragma unroll
       for (int i = 0; i < kVec; ++i)
-        ow[k][i] = *reinterpret_cast<const float4*>(ldsA + w * kMergeBytes + (mq * D + mc + 4 * i) * 4);
+        ow[k][i] = *reinterpret_cast<const float4*>(merge_tile(w) + (mq * D + mc + 4 * i) * 4);
     }
     float mmax = ml[0].x;
 #pragma unroll
