@@ -226,31 +226,7 @@ __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ 
   }
 }
 
-// The same sub-tile through registers, for the double-buffered key loops: fetch_subtile requests the rows (the
-// loads stay in flight while the previous sub-tile is multiplied), store_subtile puts them into a stage in exactly
-// the layout issue_subtile produces.  (LDS-direct loads cannot be overlapped with LDS reads of another stage: the
-// compiler cannot tell the stages apart and waits for every outstanding LDS-direct load before each LDS read.)
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-template <int D>
-__device__ __forceinline__ void fetch_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
-                                              const int32_t* __restrict__ sink_idx, int n_sink, int lane,
-                                              uintx4 (&r)[Geo<D>::kLoads]) {
-  using G = Geo<D>;
-  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
-  const int last = 31 - __builtin_clz(t.vmask);
-#pragma unroll
-  for (int i = 0; i < G::kLoads; ++i) {
-    const int slot = i * G::kRowsPerLoad + sub;
-    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
-    const int chunk = pos ^ (slot & (G::kChunks - 1));
-    r[i] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(base + (int64_t)row * sn + chunk * 8));
-  }
-}
-template <int D>
-__device__ __forceinline__ void store_subtile(char* stage, int lane, const uintx4 (&r)[Geo<D>::kLoads]) {
-#pragma unroll
-  for (int i = 0; i < Geo<D>::kLoads; ++i) *reinterpret_cast<uintx4*>(stage + i * 1024 + lane * 16) = r[i];
-}
 
 // ---------------------------------------------------------------------------------------- queries
 // Row of Q for query slot q0 + (lane % 16), or -1.  The index is fetched for every slot below max_active
@@ -511,8 +487,9 @@ __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, c
 // FUSE bit 2 set (QT = 1, dense probe layer): the scaled logits of every (query, key) are also written out, so that
 // the column attention mass of Eq. 6 needs no QK^T pass of its own.
 // FUSE bit 1 set (QT = 1 only): double-buffered key loop for launches in which a wavefront walks several sub-tiles
-// (the dense comparison): the next sub-tile's rows are requested into registers while the current one is
-// multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix cores busy.
+// (the dense comparison, the probe layer): the next sub-tile's rows travel HBM -> LDS into the wavefront's second
+// stage while the current one is multiplied, so one wavefront per SIMD keeps both the memory pipe and the matrix
+// cores busy.
 // In every case a second, small kernel merges the key splits.  (Letting the last workgroup of a head merge them
 // behind device-scope fences was measured: the fences cost ~10 us per launch, more than the launch they save.)
 template <int D, int QT, int FUSE>
@@ -620,7 +597,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
-  uintx4 rk[G::kLoads], rv[G::kLoads];  // PIPE: the sub-tile in flight
   // SHARED: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
   // the half round's sub-tile (w & 1)
   const int h_i = wave & 1, h_kv = (wave >> 1) & 1, h_first = (wave >> 2) * NLH;
@@ -644,13 +620,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows);
     if (t.vmask != 0u) {
-      if (PIPE) {
-        fetch_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, lane, rk);
-        fetch_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, lane, rv);
-      } else {
-        issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-        issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
-      }
+      issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
+      issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
     }
   }
   bf16x8 q[1][G::kKSteps];
@@ -664,10 +635,14 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   for (int ct = 0; ct < G::kColTiles; ++ct) o[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   bool first = true;
+  floatx4 kept_logits[2];  // SPILL: the raw logits of the sub-tile just multiplied, written out by the caller (see the key loops)
   auto consume = [&](const char* sK, const char* sV, uint32_t vmask, int row0) __attribute__((always_inline)) {  // one staged sub-tile into the running softmax
     floatx4 acc[1][2];
     qk_subtile<D, 1>(acc, sK, q, lane);
-    if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, row0, acc[0], p.scale_log2, lane);  // contiguous rows only (dense)
+    if (SPILL) {
+      kept_logits[0] = acc[0][0];
+      kept_logits[1] = acc[0][1];
+    }
     float ps[8];
     const float alpha = softmax_step(acc[0], vmask, g, p.scale_log2, m_run, l_run, ps);
     // the running maximum settles after a few sub-tiles: the rescale is skipped when it would multiply by one
@@ -695,10 +670,6 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows);
   };
-  if (PIPE && t.vmask != 0u) {  // the first sub-tile: registers -> this wavefront's slot of buffer A
-    store_subtile<D>(stageK, lane, rk);
-    store_subtile<D>(stageV, lane, rv);
-  }
   if (SHARED) {
     // Half rounds of two sub-tiles (wavefront w multiplies member w / QT of the pair for query tile w % QT).  While half
     // round ph is multiplied out of one buffer, the rows of half round ph + 1 travel from HBM straight into the other —
@@ -733,6 +704,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       if (vmask != 0u) {
         wait_loads();
         consume(stageK, stageV, vmask, t.row0);
+        if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, t.row0, kept_logits, p.scale_log2, lane);  // contiguous rows only (dense)
       }
       st += kWavesPerGroup;
       if (st < st_end) {
@@ -745,26 +717,31 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       }
     }
   } else {
-    // One step: the sub-tile `t` sits in this wavefront's slot of `cur`; the next one is requested into registers
-    // before `t` is multiplied and stored into the slot of `nxt` afterwards.  No barrier: the slots are private.
-    auto step = [&](const char* cur, char* nxt) {
+    // One step: the sub-tile `t` sits in this wavefront's slot of `cur`; the rows of the next one are requested straight
+    // into its slot of `nxt` (LDS-direct: no staging registers, no LDS stores) before `t` is multiplied, and are waited
+    // for afterwards, so they travel for the whole multiplication.  `cur` and `nxt` are slots of two separate arrays:
+    // the compiler can tell that the loads into one do not touch the operand reads of the other.  No barrier: the slots
+    // are private to the wavefront (which has finished reading `nxt` one step ago; wait_lds_reads makes that explicit).
+    auto step = [&](const char* cur, char* nxt) __attribute__((always_inline)) {
       const int st_next = st + kWavesPerGroup;
       SubTile tn = no_tile();
       if (st_next < st_end) tn = locate(st_next);
       if (tn.vmask != 0u) {
-        fetch_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, lane, rk);
-        fetch_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, lane, rv);
+        wait_lds_reads();
+        issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, nxt, lane);
+        issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, nxt + G::kStageBytes, lane);
       }
       if (t.vmask != 0u) consume(cur, cur + G::kStageBytes, t.vmask, t.row0);
-      if (tn.vmask != 0u) {
-        store_subtile<D>(nxt, lane, rk);
-        store_subtile<D>(nxt + G::kStageBytes, lane, rv);
-      }
+      wait_loads();
+      // the logits go out after the wait, not before it: the stores then have the whole next step to complete
+      // instead of being waited for together with the loads
+      if (SPILL && t.vmask != 0u) spill_logits(p.logits_out, h, p.dense_rows, t.row0, kept_logits, p.scale_log2, lane);
       t = tn;
       st = st_next;
     };
     char* mineA = ldsA + wave * kBufBytes;
     char* mineB = ldsB + wave * kBufBytes;
+    wait_loads();  // the first sub-tile
     while (st < st_end) {
       step(mineA, mineB);
       if (st < st_end) step(mineB, mineA);
