@@ -138,6 +138,65 @@ def parse_trace(db: str) -> int:
     return 0
 
 
+def parse_clock(db: str) -> int:
+    """Shader clock during the long launches of `bench.py --mode refresh` from one `rocprofv3 --pmc GRBM_GUI_ACTIVE` run:
+    the counter comes back summed over the 8 XCDs; cycles / 8 / duration is the clock the launch actually ran at."""
+    import sqlite3
+    c = sqlite3.connect(db)
+    rows = c.execute("select dispatch_id, kernel_name, counter_name, sum(value), min(start), max(end) from counters_collection "
+                     "where counter_name = 'GRBM_GUI_ACTIVE' group by dispatch_id, kernel_name order by dispatch_id").fetchall()
+    print("| dispatch | kernel | duration ms | GPU-active cycles (per XCD) | clock GHz |")
+    print("|---|---|---|---|---|")
+    for d, name, _, v, t0, t1 in rows:
+        dur = (t1 - t0) * 1e-9
+        if dur < 2e-3:      # the long launches only: the attention of a whole layer and the 8192^3 products
+            continue
+        short = name.replace("void focus::", "").replace("focus::", "").split("(")[0][:60]
+        print(f"| {d} | `{short}` | {dur * 1e3:.2f} | {v / 8:.3e} | {v / 8 / dur * 1e-9:.2f} |")
+    return 0
+
+
+def refresh_mode(args) -> int:
+    """Block-entry attention of one 32K layer on normal-distributed and on all-zero inputs, next to the vendor library's
+    plain bf16 product of 8192^3 on the same two kinds of input: the evidence for what bounds refresh_attn_kernel."""
+    import torch
+
+    import focus_inputs as fi
+    from paper_2602_02159_amd import binding as fb
+    dev = torch.device("cuda:0")
+    w = fi.WORKLOADS["stack32k"]
+    H, d, L, M = w.n_heads, w.head_dim, w.n_kv, w.n_ctx
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps   # ms
+
+    res = {"mode": "refresh", "shape": f"H={H} L={L} d={d}"}
+    fl = 4 * L * L * d * H
+    for kind in ("normal", "zeros"):
+        mk = (lambda *s: torch.randn(*s, device=dev).to(torch.bfloat16)) if kind == "normal" else \
+             (lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device=dev))
+        q, k, v = mk(H, L, d), mk(H, L, d), mk(H, L, d)
+        out = torch.empty_like(q)
+        sh = fb.make_shape(q, k, v, M, w.block, out)
+        ms = timed(lambda: fb.refresh_attn(q, k, v, sh, out, None), 3)
+        res[f"refresh_attn_{kind}"] = {"ms": round(ms, 3), "TFLOPps": round(fl / ms * 1e-9, 1), "frac_of_2500": round(fl / ms * 1e-9 / 2500.0, 4)}
+        del q, k, v, out
+        a, b = mk(8192, 8192), mk(8192, 8192)
+        ms = timed(lambda: torch.matmul(a, b), 10)
+        res[f"matmul_8192_{kind}"] = {"ms": round(ms, 3), "TFLOPps": round(2 * 8192 ** 3 / ms * 1e-9, 1)}
+        del a, b
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,9 +212,11 @@ def main() -> int:
     ap.add_argument("--no-full-refresh", action="store_true",
                     help="skip timing one layer of a block-entry refresh (dense attention of all M+N positions, the MFMA-bound case)")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the paper32k sparse-attention measurement (roofline_paper32k)")
-    ap.add_argument("--mode", default="bench", choices=["bench", "pmc"],
+    ap.add_argument("--parse-clock", metavar="DB", help="print the shader-clock table of a `rocprofv3 --pmc GRBM_GUI_ACTIVE` run of `--mode refresh`")
+    ap.add_argument("--mode", default="bench", choices=["bench", "pmc", "refresh"],
                     help="pmc: run a 1 GiB copy (calibration) and a few launches of every stage, nothing else; meant to be "
-                         "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
+                         "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`.  refresh: the block-entry attention and a "
+                         "plain 8192^3 bf16 product on normal-distributed and on all-zero inputs")
     ap.add_argument("--parse-pmc", nargs=2, metavar=("FETCH_DB", "WRITE_DB"),
                     help="turn the two rocprofv3 --pmc result databases of a `--mode pmc` run into profiles/hbm_traffic_<workload>.json")
     ap.add_argument("--parse-mfma", metavar="DB", help="print the MFMA utilisation table of a rocprofv3 --pmc database (see parse_mfma)")
@@ -163,6 +224,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.parse_trace:
         return parse_trace(args.parse_trace)
+    if args.parse_clock:
+        return parse_clock(args.parse_clock)
     if args.parse_mfma:
         return parse_mfma(args.parse_mfma, args.workload)
     if args.parse_pmc:
@@ -170,6 +233,9 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); run with --gpus 1", file=sys.stderr)
         return 2
+
+    if args.mode == "refresh":
+        return refresh_mode(args)
 
     import numpy as np
     import torch
