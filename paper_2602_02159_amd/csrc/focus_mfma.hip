@@ -75,6 +75,7 @@ struct SubTile {
   int row0;        // first row when contiguous (kind 0), first sink entry when kind 1
   int kind;        // 0: contiguous rows row0 .. ; 1: scattered rows sink_idx[row0 + slot]
   uint32_t vmask;  // bit s set: slot s holds a key that takes part
+  int sink_row;    // kind 1, per lane: the row that slot `lane` stages (lanes 0..31; see subtile_row)
 };
 
 __device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xffffffffu : (n > 0 ? ((1u << n) - 1u) : 0u); }
@@ -90,15 +91,23 @@ __device__ __forceinline__ uint32_t low_mask(int n) { return n >= 32 ? 0xfffffff
 //   says so (1 / 0, established once by the workgroup), or -1: not known, then a scan of 64 entries per step
 //   establishes it here.  Only lists that are not ascending pay for the all-pairs comparison.
 constexpr int kBitmapBlocks = 8192;  // largest n_b for which workgroups keep a bitmap of the kept blocks
+// A wave-uniform 4-byte read of global memory that no kernel writes while this one runs, issued as a scalar load: it
+// returns through the scalar cache instead of queueing behind the wavefront's vector loads (which return in order), and
+// a hit there is much quicker than a vector load's trip through L2.
+__device__ __forceinline__ int32_t uniform_load(const int32_t* ptr) {
+  typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+  return *(cptr_t)(uintptr_t)ptr;
+}
 __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N, int B, int n_b, int sub_per_block,
                                                   const int32_t* __restrict__ kept_blocks, int n_keep,
                                                   const int32_t* __restrict__ sink_idx, int n_sink,
                                                   const uint32_t* kept_bits = nullptr, int ascending = -1,
-                                                  int dense_rows = 0) {
+                                                  int dense_rows = 0, bool blocks_in_lds = false) {
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
+  t.sink_row = 0;
   if (dense_rows > 0) {  // every key row takes part (dense layers): sub-tile st is rows [32 st, 32 st + 32)
     t.row0 = st * kSubTile;
     t.vmask = low_mask(min(dense_rows - t.row0, kSubTile));
@@ -108,7 +117,7 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
   const int n_resp_sub = (N + kSubTile - 1) / kSubTile;
   if (st < n_blk_sub) {
     const int slot = st / sub_per_block, sub = st % sub_per_block;
-    const int b = kept_blocks[slot];
+    const int b = blocks_in_lds ? kept_blocks[slot] : uniform_load(kept_blocks + slot);
     if (b < 0 || b >= n_b) return t;
     const int first = b * B + sub * kSubTile;
     const int end = min(min((b + 1) * B, M), first + kSubTile);
@@ -166,6 +175,9 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
     }
   }
   t.vmask = (uint32_t)(__ballot(in_prompt) & 0xffffffffull) & ~bad;
+  // a slot whose sink was dropped stages the sub-tile's first valid sink instead
+  const int fallback = __shfl(mine, t.vmask != 0u ? __builtin_ctz(t.vmask) : 0, kWave);
+  t.sink_row = ((t.vmask >> (lane & 31)) & 1u) ? mine : fallback;
   return t;
 }
 
@@ -173,13 +185,9 @@ __device__ __forceinline__ SubTile locate_subtile(int st, int lane, int M, int N
 // hold no key (they are masked out of the softmax, but their V row still meets a zero probability in the PV product,
 // and 0 x inf would poison the output): past the end of a contiguous tile the tile's last valid row, for a dropped
 // sink the sub-tile's first valid sink.  `last` = highest valid slot.  Requires t.vmask != 0.
-__device__ __forceinline__ int subtile_row(const SubTile& t, int slot, int last, const int32_t* __restrict__ sink_idx,
-                                           int n_sink) {
+__device__ __forceinline__ int subtile_row(const SubTile& t, int slot, int last) {
   if (t.kind == 0) return t.row0 + min(slot, last);
-  // wave-uniform branch; the index stays inside the list even for slots that hold no key
-  const int mine = sink_idx[min(t.row0 + slot, n_sink - 1)];
-  const int fallback = sink_idx[t.row0 + __builtin_ctz(t.vmask)];
-  return ((t.vmask >> slot) & 1u) ? mine : fallback;
+  return __shfl(t.sink_row, slot, kWave);  // wave-uniform branch; the list was read once, when the sub-tile was located
 }
 
 // HBM -> LDS for one 32-row sub-tile of a [rows, D] bf16 matrix.  Lane l of load i supplies the 16 bytes that
@@ -188,8 +196,8 @@ __device__ __forceinline__ int subtile_row(const SubTile& t, int slot, int last,
 // slot that holds no key reads another row of the key set instead (subtile_row) and is masked out of the softmax.
 // Requires t.vmask != 0.
 template <int D>
-__device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
-                                              const int32_t* __restrict__ sink_idx, int n_sink, char* stage, int lane) {
+__device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t, char* stage,
+                                              int lane) {
   using G = Geo<D>;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
@@ -198,7 +206,7 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
 #pragma unroll
   for (int i = 0; i < G::kLoads; ++i) {
     const int slot = i * G::kRowsPerLoad + sub;
-    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
+    const int row = subtile_row(t, slot, last);
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, kStreamPolicy);
@@ -208,9 +216,8 @@ __device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base,
 // The loads [first, first + NL) of a sub-tile only, straight into LDS (a wavefront's share when several wavefronts
 // stage one sub-tile).  Same layout as issue_subtile.
 template <int D, int NL>
-__device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t,
-                                                   const int32_t* __restrict__ sink_idx, int n_sink, char* stage, int lane,
-                                                   int first) {
+__device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t, char* stage,
+                                                   int lane, int first) {
   using G = Geo<D>;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
@@ -219,7 +226,7 @@ __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ 
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
     const int slot = (first + i) * G::kRowsPerLoad + sub;
-    const int row = subtile_row(t, slot, last, sink_idx, n_sink);
+    const int row = subtile_row(t, slot, last);
     const int chunk = pos ^ (slot & (G::kChunks - 1));
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + (first + i) * 1024), 16, 0, kStreamPolicy);
@@ -597,6 +604,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   t.kind = 0;
   t.row0 = 0;
   t.vmask = 0u;
+  t.sink_row = 0;
   // SHARED: wavefront w stages, per half round, loads [NLH (w >> 2), +NLH) of the K (bit 1 of w clear) or V rows of
   // the half round's sub-tile (w & 1)
   const int h_i = wave & 1, h_kv = (wave >> 1) & 1, h_first = (wave >> 2) * NLH;
@@ -606,22 +614,23 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     tp.kind = 0;
     tp.row0 = 0;
     tp.vmask = 0u;
+    tp.sink_row = 0;
     const int sub = st_begin + 2 * ph + h_i;
     if (sub < st_end)
       tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending, p.dense_rows);
+                          sinks_ascending, p.dense_rows, FUSED);
     if (tp.vmask != 0u)
-      issue_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, p.sink_idx, p.n_sink,
-                                 buf + h_i * kBufBytes + h_kv * G::kStageBytes, lane, h_first);
+      issue_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, buf + h_i * kBufBytes + h_kv * G::kStageBytes, lane,
+                                 h_first);
     if (h_kv == 0 && h_first == 0 && lane == 0) maskA[2 * (ph & 1) + h_i] = tp.vmask;
   };
   if (SHARED) dma_half(0, ldsA);
   if (!SHARED && st < st_end) {
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending, p.dense_rows);
+                          sinks_ascending, p.dense_rows, FUSED);
     if (t.vmask != 0u) {
-      issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-      issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+      issue_subtile<D>(Kh, p.ksn, t, stageK, lane);
+      issue_subtile<D>(Vh, p.vsn, t, stageV, lane);
     }
   }
   bf16x8 q[1][G::kKSteps];
@@ -664,11 +673,12 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     e.kind = 0;
     e.row0 = 0;
     e.vmask = 0u;
+    e.sink_row = 0;
     return e;
   };
   auto locate = [&](int sub) {
     return locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
-                          sinks_ascending, p.dense_rows);
+                          sinks_ascending, p.dense_rows, FUSED);
   };
   if (SHARED) {
     // Half rounds of two sub-tiles (wavefront w multiplies member w / QT of the pair for query tile w % QT).  While half
@@ -678,9 +688,11 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     // is free.  Unrolled by two, so that every access names its buffer statically: the compiler then knows that an
     // LDS-direct load into one buffer does not touch the operand reads of the other and does not wait for it.
     const int n_half = (st_end - st_begin + 1) / 2;  // uniform over the workgroup
+    // a wavefront whose query tile lies past the device-side count only stages: its products would be discarded
+    const bool tile_live = q0 < n_act;
     auto consume_buf = [&](int ph, const char* buf) __attribute__((always_inline)) {
       const uint32_t vm = __builtin_amdgcn_readfirstlane(maskA[2 * (ph & 1) + kg]);
-      if (vm != 0u) {
+      if (vm != 0u && tile_live) {
         const char* cK = buf + kg * kBufBytes;
         consume(cK, cK + G::kStageBytes, vm, 0);
       }
@@ -711,8 +723,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
         t = locate(st);
         if (t.vmask != 0u) {
           wait_lds_reads();
-          issue_subtile<D>(Kh, p.ksn, t, p.sink_idx, p.n_sink, stageK, lane);
-          issue_subtile<D>(Vh, p.vsn, t, p.sink_idx, p.n_sink, stageV, lane);
+          issue_subtile<D>(Kh, p.ksn, t, stageK, lane);
+          issue_subtile<D>(Vh, p.vsn, t, stageV, lane);
         }
       }
     }
@@ -728,8 +740,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       if (st_next < st_end) tn = locate(st_next);
       if (tn.vmask != 0u) {
         wait_lds_reads();
-        issue_subtile<D>(Kh, p.ksn, tn, p.sink_idx, p.n_sink, nxt, lane);
-        issue_subtile<D>(Vh, p.vsn, tn, p.sink_idx, p.n_sink, nxt + G::kStageBytes, lane);
+        issue_subtile<D>(Kh, p.ksn, tn, nxt, lane);
+        issue_subtile<D>(Vh, p.vsn, tn, nxt + G::kStageBytes, lane);
       }
       if (t.vmask != 0u) consume(cur, cur + G::kStageBytes, t.vmask, t.row0);
       wait_loads();
@@ -1329,6 +1341,7 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
   auto tile_of = [&](int s) {
     SubTile t;
     t.kind = 0;
+    t.sink_row = 0;
     t.row0 = s * kSubTile;
     t.vmask = low_mask(min(p.L - t.row0, kSubTile));
     return t;
@@ -1337,7 +1350,7 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) qrow[qt] = fetch_q_row(p.active_idx, q_base + qt * kQTile, p.max_active, p.n_gen, lane);
   SubTile t = tile_of(st < st_end ? st : 0);
-  if (st < st_end) issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
+  if (st < st_end) issue_subtile<D>(Kh, p.ksn, t, stageK, lane);
 
   bf16x8 q[NQT][G::kKSteps];
 #pragma unroll
@@ -1370,7 +1383,7 @@ __global__ __launch_bounds__(256, 2) void qk_logits_kernel(const LogitArgs p) {
     if (st < st_end) {
       t = tile_of(st);
       wait_lds_reads();
-      issue_subtile<D>(Kh, p.ksn, t, nullptr, 0, stageK, lane);
+      issue_subtile<D>(Kh, p.ksn, t, stageK, lane);
     }
     if (MODE == 2) {
       float colsum[8];
