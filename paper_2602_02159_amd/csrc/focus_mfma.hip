@@ -546,6 +546,14 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   TopkShared& topk_sm = *reinterpret_cast<TopkShared*>(topk_raw);
   __shared__ int32_t kept_sh[FUSED ? kFusedMaxBlocks : 1];
   const int32_t* kept_blocks = p.kept_blocks;
+  // With the Top-C prologue ahead, the query rows are requested before it (their two round trips — row ids, then rows —
+  // pass while the relevances are summed and ranked); without it they follow the first K/V requests (see below).
+  bf16x8 q[1][G::kKSteps];
+  int qrow_early = -1;
+  if (FUSED) {
+    qrow_early = fetch_q_row(p.active_idx, q0, p.max_active, p.n_gen, lane);
+    load_q_tile<D>(q[0], Qh, p.qsn, qrow_early, lane);
+  }
   if (FUSED) {
     // R_b = (1 / (|I_focus| H)) sum_h part[h, b] for b = threadIdx.x (n_b <= 256), then Top-C
     const int tid = threadIdx.x;
@@ -599,7 +607,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
   const int st_begin = split * p.per_split;
   const int st_end = min(st_begin + p.per_split, p.n_sub);
   int st = st_begin + slot;
-  const int qrow = fetch_q_row(p.active_idx, q0, p.max_active, p.n_gen, lane);
+  const int qrow = FUSED ? qrow_early : fetch_q_row(p.active_idx, q0, p.max_active, p.n_gen, lane);
   SubTile t;
   t.kind = 0;
   t.row0 = 0;
@@ -633,8 +641,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       issue_subtile<D>(Vh, p.vsn, t, stageV, lane);
     }
   }
-  bf16x8 q[1][G::kKSteps];
-  load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
+  if (!FUSED) load_q_tile<D>(q[0], Qh, p.qsn, qrow, lane);
   const int n_act = p.counts ? min(max(p.counts[1], 0), p.max_active) : p.max_active;
   mask_q_tile<D>(q[0], q0, n_act, lane);
 
