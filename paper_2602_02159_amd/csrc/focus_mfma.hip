@@ -718,22 +718,13 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       __syncthreads();
     }
   } else if (!PIPE) {
-    while (st < st_end) {
-      const uint32_t vmask = t.vmask;
-      if (vmask != 0u) {
-        wait_loads();
-        consume(stageK, stageV, vmask, t.row0);
-        if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, t.row0, kept_logits, p.scale_log2, lane);  // contiguous rows only (dense)
-      }
-      st += kWavesPerGroup;
-      if (st < st_end) {
-        t = locate(st);
-        if (t.vmask != 0u) {
-          wait_lds_reads();
-          issue_subtile<D>(Kh, p.ksn, t, stageK, lane);
-          issue_subtile<D>(Vh, p.vsn, t, stageV, lane);
-        }
-      }
+    // one sub-tile per wavefront at most (the launcher picks this variant only when a split holds no more sub-tiles
+    // than the workgroup has wavefronts): no key loop, and none of its code — these launches are a few microseconds
+    // long and start with a cold instruction cache, so every KB of code they walk through shows in the run time
+    if (t.vmask != 0u) {
+      wait_loads();
+      consume(stageK, stageV, t.vmask, t.row0);
+      if (SPILL) spill_logits(p.logits_out, h, p.dense_rows, t.row0, kept_logits, p.scale_log2, lane);  // contiguous rows only (dense)
     }
   } else {
     // One step: the sub-tile `t` sits in this wavefront's slot of `cur`; the rows of the next one are requested straight
@@ -864,6 +855,7 @@ template <int D, int QT>
 static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fused, hipStream_t st) {
   const dim3 grid = a.groups_first ? dim3(p.q_groups, a.H, p.n_split) : dim3(p.n_split, a.H, p.q_groups);
   const bool pipe = QT == 1 && p.pipelined;  // shared sub-tiles (QT > 1) have their own pipelining
+  if (QT == 1 && !pipe && p.per_split > kWavesPerGroup) return hipErrorInvalidValue;  // the loop-free variant: one sub-tile per wavefront
   const dim3 block(QT == 4 ? 512 : 256);
   if (a.logits_out != nullptr) {  // dense probe layer with the logits spilled; QT == 1 by construction
     if (QT != 1 || fused) return hipErrorInvalidValue;
