@@ -420,12 +420,11 @@ struct AttnArgs {
 
 // Merge of per-split partial results for one (head, active row a): out = sum_s f_s O_s / sum_s f_s l_s with
 // f_s = exp2(m_s - running max), splits taken in index order, eight loads in flight at a time.  Thread = D/16 columns.
-template <int D, int kBatch>
+template <int D, int kBatch, int kPerThread>
 __device__ __forceinline__ void merge_splits(const float* __restrict__ part_o, const float* __restrict__ part_ml, int h, int a,
                                              int mc, int q_pad, int n_split, int max_active, int n_act, uint16_t* __restrict__ out,
                                              int64_t osh, int64_t osn, float* __restrict__ lse, float* __restrict__ lse2,
                                              bool write_lse) {
-  constexpr int kPerThread = D / 16;
   constexpr int kVec = kPerThread / 4;
   const int64_t row0 = ((int64_t)h * q_pad + a) * n_split;
   const float2* ml = reinterpret_cast<const float2*>(part_ml) + row0;
@@ -833,7 +832,8 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
 }
 
 // Merge of the per-split partial results: out = sum_s f_s O_s / sum_s f_s l_s, f_s = exp2(m_s - max m).
-// One workgroup per (head, 16 queries); thread = (query, D/16 columns).  Fixed order over splits; the loads of
+// One workgroup per (head, 16 queries, 64 output columns); thread = (query, 4 columns) — the column halves of d = 128 go
+// to two workgroups, which halves what one compute unit has to pull in.  Fixed order over splits; the loads of
 // kBatch splits are issued together — and together with the load of the device-side query count, which is only looked
 // at when the row is stored — so the kernel is one memory round trip long for up to kBatch splits.
 template <int D, int kBatch>
@@ -842,13 +842,14 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
                                                            const int32_t* __restrict__ counts, int max_active, int q_pad,
                                                            int n_split, uint16_t* __restrict__ out, int64_t osh, int64_t osn,
                                                            float* __restrict__ lse, float* __restrict__ lse2) {
+  constexpr int kPerThread = 4;
   const int h = blockIdx.y;
   const int a = blockIdx.x * 16 + (threadIdx.x >> 4);
-  const int mc = (threadIdx.x & 15) * (D / 16);
+  const int mc = blockIdx.z * 64 + (threadIdx.x & 15) * kPerThread;
   if (a >= max_active) return;  // host-side capacity of the active list; rows below it exist in the workspace
   const int n_act = counts ? min(max(counts[1], 0), max_active) : max_active;
-  merge_splits<D, kBatch>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, n_act, out, osh, osn, lse, lse2,
-                          (threadIdx.x & 15) == 0);
+  merge_splits<D, kBatch, kPerThread>(part_o, part_ml, h, a, mc, q_pad, n_split, max_active, n_act, out, osh, osn, lse, lse2,
+                                      blockIdx.z == 0 && (threadIdx.x & 15) == 0);
 }
 
 template <int D, int QT>
@@ -874,10 +875,10 @@ static hipError_t launch_attn_t(const AttnArgs& a, const SplitPlan& p, bool fuse
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_split == 1) return e;
   if (p.n_split <= 8)
-    hipLaunchKernelGGL((attn_combine_kernel<D, 8>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
+    hipLaunchKernelGGL((attn_combine_kernel<D, 8>), dim3(p.q_tiles, a.H, D / 64), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
                        a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
   else
-    hipLaunchKernelGGL((attn_combine_kernel<D, 16>), dim3(p.q_tiles, a.H), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
+    hipLaunchKernelGGL((attn_combine_kernel<D, 16>), dim3(p.q_tiles, a.H, D / 64), dim3(256), 0, st, a.part_o, a.part_ml, a.counts,
                        a.max_active, a.q_pad, a.n_split, a.out, a.osh, a.osn, a.lse, a.lse2_out);
   return hipGetLastError();
 }
