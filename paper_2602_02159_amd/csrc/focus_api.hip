@@ -32,7 +32,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 constexpr int kAttnGroups = 1024;        // one sub-tile per wavefront at the 3 % keep configurations
 constexpr int kAttnGroupsShared = 512;   // several query tiles per workgroup: two resident workgroups per compute unit
 constexpr int kAttnGroupsPipe = 256;     // many sub-tiles per wavefront: one resident workgroup per compute unit
-constexpr int kLogitGroups = 2048;       // probe-layer logits
+constexpr int kLogitGroups = 4096;       // sink scoring: measured best of 1024 .. 8192 (short workgroups even out the tail of the scan)
 
 static void plan_queries(SplitPlan& p, int max_active) {
   p.q_tiles = ceil_div(max_active, kQTile);
