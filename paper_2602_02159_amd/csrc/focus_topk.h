@@ -115,6 +115,14 @@ __device__ __forceinline__ void wave_topk(const uint32_t* keys, int n, int k, in
 #pragma unroll
       for (int r = 0; r < KPL; ++r) cnt += (uint32_t)__popcll(__ballot(kv[r] >= cand));
       if (cnt >= k_eff) T = cand;
+      // Exactly k keys reach this threshold: they are the k largest, whatever their lower bits.  T = cand - 1 makes
+      // "key > T" below select exactly them (the count of keys equal to T still to take comes out as zero).  With
+      // distinct keys the search thus ends at the first bit in which the k-th and the (k+1)-th largest differ — about
+      // a dozen steps instead of 32; only a tie at the boundary walks all 32.
+      if (cnt == k_eff) {
+        T = cand - 1u;
+        break;
+      }
     }
   } else {
     T = 0xffffffffu;
@@ -166,7 +174,12 @@ __device__ __forceinline__ bool wave_select1(uint32_t key1, int k, uint32_t& pos
     T = 0;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = T | (1u << bit);
-      if ((uint32_t)__popcll(__ballot(key1 >= cand)) >= k_eff) T = cand;
+      const uint32_t cnt = (uint32_t)__popcll(__ballot(key1 >= cand));
+      if (cnt >= k_eff) T = cand;
+      if (cnt == k_eff) {  // exactly k keys reach cand: they are the answer (see wave_topk)
+        T = cand - 1u;
+        break;
+      }
     }
   }
   const unsigned long long below = (1ull << lane) - 1ull;
