@@ -689,6 +689,9 @@ def main() -> int:
         "ms_per_step_warm_caches": round(ms_warm, 4),
         "ms_per_step_block_means_recomputed": round(ms_recomputed, 4),
         "ms_per_step_sinks_from_probe_layer": round(ms_probe, 4),
+        # the probe layer is a dense layer the model runs in any case (Alg. 1: layers up to l_dense are dense): what the sinks
+        # cost on top of it = probe-layer call - dense attention of the same queries, per launch
+        "us_sinks_on_top_of_the_dense_probe_layer": round(stages["probe_layer"]["us_per_launch"] - stages["dense_attn"]["us_per_launch"], 3),
         "ms_per_step_dense_attention": round(ms_dense, 4),
         "dense_over_sparse": round(ms_dense / ms_step, 2),
         "dense_step_hbm_frac": round(dense_bytes / ms_dense * 1e-6 / HBM_PEAK_GBS, 4),
