@@ -197,6 +197,50 @@ def refresh_mode(args) -> int:
     return 0
 
 
+def decoder_mode(args) -> int:
+    """Alg. 1 over a generation block of the whole 32-layer stack at the 32K shape, through FocusDecoder's two HIP graphs:
+    the block entry (per layer: caches rewritten + block means, dense attention of every position) and one step (selection,
+    then per layer the cache update of the active rows and dense attention up to the probe layer, the probe layer, the sparse
+    layers from the block means of the entry).  Inputs: normal-distributed bf16 states, uniform confidences.  Not the
+    driver's metric: context for it (what the method's attention path costs per block entry and per step)."""
+    import torch
+
+    import focus_inputs as fi
+    from paper_2602_02159_amd.step import FocusDecoder
+    dev = torch.device("cuda:0")
+    w = fi.WORKLOADS["stack32k"]
+    n_layers, l_dense = w.n_layers, w.probe_layer
+    dec = FocusDecoder(n_layers, l_dense, 0, w.n_heads, w.head_dim, w.n_ctx, w.n_resp, w.n_gen, w.n_ctx, w.block, w.k_focus,
+                       w.window, w.n_keep, w.n_sink, dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    for l in range(n_layers):
+        for t in (dec.q_all[l], dec.k_all[l], dec.v_all[l], dec.q[l], dec.k_new[l], dec.v_new[l]):
+            t.copy_(torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32))
+    dec.conf.copy_(torch.rand(w.n_gen, generator=gen, device=dev))
+    dec.capture()
+    torch.cuda.synchronize()
+
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps   # ms
+
+    ms_entry = timed(dec.run_entry, 1)
+    dec.run_step()
+    ms_step = timed(dec.run_step, args.steps)
+    n_sparse = sum(dec.is_sparse(l) for l in range(n_layers))
+    print(json.dumps({"mode": "decoder", "workload": w.name, "layers": n_layers, "dense_layers_incl_probe": l_dense + 1,
+                      "sparse_layers": n_sparse, "ms_block_entry": round(ms_entry, 2), "ms_per_step": round(ms_step, 4),
+                      "steps_timed": args.steps, "launch": "two HIP graphs (block entry, step)",
+                      "n_active": int(dec.counts.cpu()[1])}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,7 +257,7 @@ def main() -> int:
                     help="skip timing one layer of a block-entry refresh (dense attention of all M+N positions, the MFMA-bound case)")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the paper32k sparse-attention measurement (roofline_paper32k)")
     ap.add_argument("--parse-clock", metavar="DB", help="print the shader-clock table of a `rocprofv3 --pmc GRBM_GUI_ACTIVE` run of `--mode refresh`")
-    ap.add_argument("--mode", default="bench", choices=["bench", "pmc", "refresh"],
+    ap.add_argument("--mode", default="bench", choices=["bench", "pmc", "refresh", "decoder"],
                     help="pmc: run a 1 GiB copy (calibration) and a few launches of every stage, nothing else; meant to be "
                          "run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`.  refresh: the block-entry attention and a "
                          "plain 8192^3 bf16 product on normal-distributed and on all-zero inputs")
@@ -234,6 +278,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); run with --gpus 1", file=sys.stderr)
         return 2
 
+    if args.mode == "decoder":
+        return decoder_mode(args)
     if args.mode == "refresh":
         return refresh_mode(args)
 
