@@ -5,8 +5,9 @@
 // Output: the selected indices in ascending order, then -1 up to k, and the count.
 //
 // Three paths, one workgroup each:
-//   * n <= 256, small k : every wavefront selects among its own 64 candidates (one key per lane) by a 32-step
-//                     bitwise search over ballot popcounts, then one wavefront selects among the winners.
+//   * n <= 256, small k : every wavefront selects among its own 64 candidates (one key per lane) by a bitwise
+//                     search over ballot popcounts (at most 32 steps; it ends as soon as exactly k keys clear the
+//                     threshold under test), then one wavefront selects among the winners.
 //   * n <= blockDim : the keys are staged in LDS and ONE wavefront, holding up to 16 keys per lane in registers,
 //                     finds the k-th largest key by the same bitwise search (no barriers, no O(n^2) compares),
 //                     then emits the selection in index order from ballot prefix counts.
@@ -65,8 +66,8 @@ struct TopkShared {
 };
 
 // Top-k of up to 64 * KPL keys by ONE wavefront, no barriers.  keys[i] = order key + 1, or 0 for "not a candidate";
-// lane l holds keys[l * KPL .. l * KPL + KPL).  A bitwise search finds T, the k-th largest key (32 steps of KPL
-// compares and ballot popcounts); everything above T is selected, and of the keys equal to T the ones with the
+// lane l holds keys[l * KPL .. l * KPL + KPL).  A bitwise search finds T, the k-th largest key (at most 32 steps of
+// KPL compares and ballot popcounts); everything above T is selected, and of the keys equal to T the ones with the
 // lowest indices until k are reached.  Output positions come from ballot prefix counts, so `out` is ascending.
 // Writes out[0..k) = base + index, or remap[index] when remap is given (tail -1), flags[0..n) if not null, and *total.
 // Must be called by all 64 lanes of one wavefront.
@@ -197,7 +198,7 @@ __device__ __forceinline__ bool wave_select1(uint32_t key1, int k, uint32_t& pos
 // instruction cache, and their run time is mostly instruction fetch).
 // MAXN: compile-time bound on n (256, 512 or 1024): wider selections than needed are not compiled in.
 //  - MAXN <= 256 and k * (number of wavefronts) <= 64: a two-round tournament.  Every wavefront selects the top k of
-//    its own 64 candidates (one key per lane, 32 ballot steps), the winners meet in LDS in index order and one
+//    its own 64 candidates (one key per lane, at most 32 ballot steps), the winners meet in LDS in index order and one
 //    wavefront selects the top k of those.
 //  - otherwise the keys go to LDS and ONE wavefront selects among all of them (wave_topk) while the others wait.
 template <int MAXN = kTopkThreads, class KeyFn>
