@@ -560,7 +560,31 @@ def main() -> int:
     ub = 2 * 2 * L * H * d * 2 + H * n_b * d * 4
     stages["cache_refresh"] = {"us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": ub, "alg_flops": 0,
                                "GBps": round(ub / us * 1e-3, 1), "TFLOPps": 0.0, "hbm_frac": round(ub / us * 1e-3 / HBM_PEAK_GBS, 4)}
-    del vl, k_cache, v_cache, kbar_r
+    # dense comparison with ALL positions of the generation block as queries (what a decoder without the query selection of
+    # Eq. 4 / Eq. 5 runs in every layer): every key, every query of the block; rotated over the layers of the two input sets
+    all_q = torch.arange(w.n_gen, dtype=torch.int32, device=dev)
+    all_counts = torch.tensor([w.n_gen, w.n_gen], dtype=torch.int32, device=dev)
+    all_blocks = torch.arange(n_b, dtype=torch.int32, device=dev)
+    out_all_q = torch.empty(H, w.n_gen, d, dtype=torch.bfloat16, device=dev)
+    d2_layers = [lay for so in steps_obj for lay in so.layers]
+    d2_shapes = [fb.make_shape(qq, kk, vv, M, w.block, out_all_q) for qq, kk, vv in d2_layers]
+    d2_ws = torch.empty(fb.workspace_bytes(fb.FN_SPARSE_ATTN, d2_shapes[0], w.n_gen, n_b, 0), dtype=torch.uint8, device=dev)
+    d2_rot = [0]
+
+    def d2_call():
+        i = d2_rot[0] % len(d2_layers)
+        d2_rot[0] += 1
+        qq, kk, vv = d2_layers[i]
+        fb.sparse_attn(qq, all_q, all_counts, kk, vv, d2_shapes[i], all_blocks, n_b, None, 0, out_all_q, None, d2_ws)
+
+    us = time_call(d2_call, reps=len(d2_layers), replays=4)
+    db2 = 2 * L * H * d * 2 + 2 * w.n_gen * H * d * 2
+    stages["dense_attn_all_block_queries"] = {
+        "us_per_launch": round(us, 3), "launches_per_step": 0, "alg_bytes": db2, "alg_flops": 4 * w.n_gen * L * d * H,
+        "GBps": round(db2 / us * 1e-3, 1), "TFLOPps": round(4 * w.n_gen * L * d * H / us * 1e-6, 3),
+        "hbm_frac": round(db2 / us * 1e-3 / HBM_PEAK_GBS, 4),
+        "note": f"dense attention of all {w.n_gen} positions of the generation block over every key, one layer"}
+    del vl, k_cache, v_cache, kbar_r, d2_ws
     if not args.no_full_refresh:
         # block entry (Alg. 1): every position is active and attends to every key; 4 L^2 d H flops against the bf16 MFMA peak
         q_all = torch.randn(H, L, d, device=dev).to(torch.bfloat16)
