@@ -195,26 +195,11 @@ __device__ __forceinline__ int subtile_row(const SubTile& t, int slot, int last)
 // the swizzle that position holds logical chunk (l mod chunks) ^ (row mod chunks).  No load is predicated: a
 // slot that holds no key reads another row of the key set instead (subtile_row) and is masked out of the softmax.
 // Requires t.vmask != 0.
-template <int D>
-__device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t, char* stage,
-                                              int lane) {
-  using G = Geo<D>;
-  typedef const __attribute__((address_space(1))) void* gptr_t;
-  typedef __attribute__((address_space(3))) void* lptr_t;
-  const int sub = lane / G::kChunks, pos = lane % G::kChunks;
-  const int last = 31 - __builtin_clz(t.vmask);
-#pragma unroll
-  for (int i = 0; i < G::kLoads; ++i) {
-    const int slot = i * G::kRowsPerLoad + sub;
-    const int row = subtile_row(t, slot, last);
-    const int chunk = pos ^ (slot & (G::kChunks - 1));
-    const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
-    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, kStreamPolicy);
-  }
-}
-
-// The loads [first, first + NL) of a sub-tile only, straight into LDS (a wavefront's share when several wavefronts
-// stage one sub-tile).  Same layout as issue_subtile.
+// The loads [first, first + NL) of a sub-tile, straight into LDS (all of them, or a wavefront's share when several
+// wavefronts stage one sub-tile).  A whole contiguous sub-tile — the common case — takes the short way: one scalar base
+// address per sub-tile plus per-lane byte offsets that depend on the lane and the load only (the compiler keeps them
+// across a key loop), so a request costs no per-lane address arithmetic; ragged and scattered sub-tiles work out a row
+// per lane and load.
 template <int D, int NL>
 __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t, char* stage,
                                                    int lane, int first) {
@@ -222,6 +207,17 @@ __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ 
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
   const int sub = lane / G::kChunks, pos = lane % G::kChunks;
+  if (t.kind == 0 && t.vmask == 0xffffffffu) {  // wave-uniform
+    const char* tile = reinterpret_cast<const char*>(base + (int64_t)__builtin_amdgcn_readfirstlane(t.row0) * sn);
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int slot = (first + i) * G::kRowsPerLoad + sub;
+      const int chunk = pos ^ (slot & (G::kChunks - 1));
+      const uint32_t off = (uint32_t)slot * (uint32_t)(sn * 2) + (uint32_t)(chunk * 16);  // a sub-tile spans < 4 GB
+      __builtin_amdgcn_global_load_lds((gptr_t)(tile + off), (lptr_t)(stage + (first + i) * 1024), 16, 0, kStreamPolicy);
+    }
+    return;
+  }
   const int last = 31 - __builtin_clz(t.vmask);
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
@@ -231,6 +227,11 @@ __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ 
     const uint16_t* src = base + (int64_t)row * sn + chunk * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + (first + i) * 1024), 16, 0, kStreamPolicy);
   }
+}
+template <int D>
+__device__ __forceinline__ void issue_subtile(const uint16_t* __restrict__ base, int64_t sn, const SubTile& t, char* stage,
+                                              int lane) {
+  issue_subtile_part<D, Geo<D>::kLoads>(base, sn, t, stage, lane, 0);
 }
 
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
@@ -626,12 +627,21 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     if (sub < st_end)
       tp = locate_subtile(sub, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows, FUSED);
+    // (the lane id goes through an empty asm so that the per-lane byte offsets are worked out again in every half
+    // round instead of being kept in registers across the loop: this variant has none to spare)
+    int lane_now = lane;
+    asm volatile("" : "+v"(lane_now));
     if (tp.vmask != 0u)
-      issue_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, buf + h_i * kBufBytes + h_kv * G::kStageBytes, lane,
+      issue_subtile_part<D, NLH>(h_kv ? Vh : Kh, h_kv ? p.vsn : p.ksn, tp, buf + h_i * kBufBytes + h_kv * G::kStageBytes, lane_now,
                                  h_first);
     if (h_kv == 0 && h_first == 0 && lane == 0) maskA[2 * (ph & 1) + h_i] = tp.vmask;
   };
-  if (SHARED) dma_half(0, ldsA);
+  // SHARED: the first two half rounds are requested before anything else is waited for (the query rows take two
+  // dependent round trips; both buffers are free until the loop starts)
+  if (SHARED) {
+    dma_half(0, ldsA);
+    if (st_begin + 2 < st_end) dma_half(1, ldsB);
+  }
   if (!SHARED && st < st_end) {
     t = locate_subtile(st, lane, p.M, p.N, p.B, p.n_b, p.sub_per_block, kept_blocks, p.n_keep, p.sink_idx, p.n_sink, kept_bits,
                           sinks_ascending, p.dense_rows, FUSED);
@@ -706,7 +716,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
     wait_loads();
     __syncthreads();  // half round 0 is staged
     for (int ph = 0; ph < n_half; ph += 2) {
-      if (ph + 1 < n_half) dma_half(ph + 1, ldsB);  // buffer B was last read in half round ph - 1, before the last barrier
+      if (ph > 0 && ph + 1 < n_half) dma_half(ph + 1, ldsB);  // buffer B was last read in half round ph - 1, before the last barrier
       consume_buf(ph, ldsA);
       wait_loads();
       __syncthreads();  // half round ph + 1 is staged; everyone is done with buffer A
