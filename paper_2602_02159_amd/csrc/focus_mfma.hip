@@ -565,7 +565,7 @@ __global__ __launch_bounds__((QT == 4 ? 512 : 256), (QT == 4 ? 4 : ((FUSE & 2) =
       key = order_key(r);
       return true;
     };
-    block_topk<kFusedMaxBlocks>(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);  // n_b <= 256 = blockDim.x
+    block_topk<kFusedMaxBlocks, true>(keyfn, p.n_b, p.n_keep, kept_sh, nullptr, nullptr, topk_sm);  // n_b <= 256 = blockDim.x; first use of topk_sm
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
       if (p.scores_out && tid < p.n_b) p.scores_out[tid] = r;
       if (tid < p.n_keep) p.kept_out[tid] = kept_sh[tid];

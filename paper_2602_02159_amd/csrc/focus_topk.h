@@ -201,7 +201,8 @@ __device__ __forceinline__ bool wave_select1(uint32_t key1, int k, uint32_t& pos
 //    its own 64 candidates (one key per lane, at most 32 ballot steps), the winners meet in LDS in index order and one
 //    wavefront selects the top k of those.
 //  - otherwise the keys go to LDS and ONE wavefront selects among all of them (wave_topk) while the others wait.
-template <int MAXN = kTopkThreads, class KeyFn>
+// FRESH: the caller vouches that nobody is still reading `sm` from an earlier use (saves a barrier).
+template <int MAXN = kTopkThreads, bool FRESH = false, class KeyFn>
 __device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, int k, int32_t* out, uint8_t* flags,
                                                      TopkShared& sm) {
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -217,15 +218,17 @@ __device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, i
       if (flags && tid < n) flags[tid] = (uint8_t)sel;
       return cnt;
     }
-    __syncthreads();  // the caller may still be reading sm from an earlier use
-    if (tid < kWave) sm.keys[tid] = 0u;
-    if (flags && tid < n) flags[tid] = 0;
-    __syncthreads();
+    if (!FRESH) __syncthreads();  // the caller may still be reading sm from an earlier use
+    // every one of the 64 slots of the second round is written exactly once: a winner, or zero — by the lanes k_eff .. k - 1
+    // of the wavefront that leaves slots empty, and by the first wavefront for the slots no wavefront owns
     if (sel) {
       const int slot = (tid >> 6) * k + (int)pos;  // ascending slot <=> ascending candidate index
       sm.keys[slot] = key1;
       sm.hist[slot] = (uint32_t)tid;
     }
+    if ((tid & 63) >= (int)cnt && (tid & 63) < k) sm.keys[(tid >> 6) * k + (tid & 63)] = 0u;
+    if (tid >= n_waves * k && tid < kWave) sm.keys[tid] = 0u;
+    if (flags && tid < n) flags[tid] = 0;
     __syncthreads();
     if (tid < kWave) {
       uint32_t pos2, cnt2;
@@ -262,14 +265,14 @@ __device__ __forceinline__ uint32_t block_topk_small(const KeyFn keyfn, int n, i
 // `dense_values`, if not null, is a 16-byte aligned float array whose element i is the value of candidate i and
 // every i < n is a candidate: the large-n path then fetches each thread's run with 16-byte loads.
 // MAXN > 0: the caller guarantees n <= min(blockDim.x, MAXN); the radix path is not compiled in.
-template <int MAXN = 0, class KeyFn>
+template <int MAXN = 0, bool FRESH = false, class KeyFn>
 __device__ __forceinline__ void block_topk(const KeyFn keyfn, int n, int k, int32_t* out, int32_t* out_count, uint8_t* flags,
                                            TopkShared& sm, const float* dense_values = nullptr) {
   const int tid = threadIdx.x, nt = blockDim.x;
   uint32_t total;
 
   if (MAXN > 0 || n <= nt) {
-    total = block_topk_small<(MAXN > 0 ? MAXN : kTopkThreads)>(keyfn, n, k, out, flags, sm);
+    total = block_topk_small<(MAXN > 0 ? MAXN : kTopkThreads), FRESH>(keyfn, n, k, out, flags, sm);
   } else {
     // ---- radix select; each thread owns the contiguous run [c0, c1)
     const int chunk = (((n + nt - 1) / nt) + 3) & ~3;  // a multiple of 4, so runs start 16-byte aligned
