@@ -207,7 +207,7 @@ __device__ __forceinline__ void issue_subtile_part(const uint16_t* __restrict__ 
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
   const int sub = lane / G::kChunks, pos = lane % G::kChunks;
-  if (t.kind == 0 && t.vmask == 0xffffffffu) {  // wave-uniform
+  if (t.kind == 0 && t.vmask == 0xffffffffu && sn < (int64_t(1) << 26)) {  // wave-uniform; 31 rows of the stride fit 32 bits
     const char* tile = reinterpret_cast<const char*>(base + (int64_t)__builtin_amdgcn_readfirstlane(t.row0) * sn);
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
