@@ -509,7 +509,7 @@ __global__ __launch_bounds__(512) void column_mass_kernel(const float* __restric
     mass = mass_sh[threadIdx.x];
     col_mass[j] = mass;
   }
-  if (cand != nullptr && blockIdx.x * kMassKeys < M) {  // uniform over the workgroup
+  if (cand != nullptr && (int)blockIdx.x * kMassKeys < M) {  // uniform over the workgroup
     if (threadIdx.x < 256) ckeys[threadIdx.x] = (threadIdx.x < kMassKeys && j < M) ? order_key(mass) + 1u : 0u;
     __syncthreads();
     if (threadIdx.x < kWave)
